@@ -1,0 +1,237 @@
+/*
+ * fax.h -- C ABI of the per-device Transformer training step for MI355X (gfx950).
+ *
+ * The paper's framework compiles one function per device: the training step of
+ * a decoder-only Transformer (Fig. 1), whose phases are the forward pass, the
+ * loss and the backward pass (Fig. 4), followed by the Adam update (Table 1
+ * caption), on that device's shard of the data-parallel x tensor-parallel mesh
+ * (Sec. 2.2, Sec. 3.2).  This library is that per-device function as
+ * hand-written HIP kernels.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers unless a comment says "host".
+ *     Structs (dims, pointer tables) are HOST memory, read during the call only.
+ *   - The caller owns every buffer: inputs, outputs, saved activations,
+ *     gradients, optimizer state, workspace.  The library allocates nothing
+ *     and keeps no pointer after a call returns.
+ *   - Work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
+ *     default stream); the calls do not synchronise.  Outputs are valid once
+ *     the caller has synchronised the stream.
+ *   - Return value: FAX_OK or a negative FaxStatus; fax_last_error() gives the
+ *     text for the calling thread.  Arguments are validated on the host before
+ *     the first launch, so a failed call has enqueued nothing.
+ *   - Tensors are row-major.  Activations are [B, S, D] = [T, D] with T = B*S.
+ *     Weight matrices are [in, out], applied as y = x W + b.  The fused QKV
+ *     projection has 3*H*dh columns ordered [Q | K | V], head-major within each.
+ *   - dtype FAX_BF16: activations, parameters and activation gradients are
+ *     bfloat16, every accumulation, statistic and softmax is fp32.
+ *     dtype FAX_F32: everything is fp32 with true fp32 multiply-add.
+ *     Parameter GRADIENTS are fp32 for both dtypes.
+ *   - Pointers must be 16-byte aligned.
+ */
+#ifndef FAX_H
+#define FAX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum FaxStatus {
+  FAX_OK = 0,
+  FAX_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, inconsistent dims, misalignment */
+  FAX_ERR_UNSUPPORTED = -2, /* a shape or option no kernel here covers */
+  FAX_ERR_WORKSPACE = -3,   /* workspace smaller than fax_*_workspace_bytes() */
+  FAX_ERR_HIP = -4          /* a HIP runtime or launch error */
+} FaxStatus;
+
+enum { FAX_F32 = 0, FAX_BF16 = 1 };
+enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
+
+/* FaxBlockDims.flags */
+#define FAX_FLAG_TP_PARTIAL 1u /* also emit the pre-reduction partial sums (Sec. 3.2) */
+
+/* FaxModelDims.flags */
+#define FAX_FLAG_SKIP_UPDATE 1u /* fax_train_step: stop after the gradients */
+
+/* Shape of one decoder block as one device holds it.  H and F are the LOCAL
+ * head count and feed-forward width; H*dh need not equal D (a tensor-parallel
+ * share, Sec. 3.2). */
+typedef struct FaxBlockDims {
+  int32_t B, S, D, H, dh, F;
+  int32_t dtype;  /* FAX_F32 | FAX_BF16 */
+  int32_t gelu;   /* FAX_GELU_TANH | FAX_GELU_ERF */
+  float ln_eps;   /* LayerNorm epsilon, added to the biased variance */
+  uint32_t flags;
+} FaxBlockDims;
+
+/* The twelve parameter tensors of a block, or twelve buffers shaped like them
+ * (fp32 master copies, Adam moments, gradients).
+ *   ln1_g, ln1_b [D]; wqkv [D, 3*H*dh]; bqkv [3*H*dh]; wo [H*dh, D]; bo [D];
+ *   ln2_g, ln2_b [D]; w1 [D, F]; b1 [F]; w2 [F, D]; b2 [D]. */
+typedef struct FaxBlockTensors {
+  void *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} FaxBlockTensors;
+
+/* Byte offsets of each tensor inside the saved-activation buffer that
+ * fax_block_fwd fills and fax_block_bwd reads.  Element type is dims.dtype
+ * except the four LayerNorm statistics and lse, which are fp32. */
+typedef struct FaxSavedLayout {
+  size_t h1;    /* [T, D]      LN1(x) */
+  size_t qkv;   /* [T, 3*H*dh] */
+  size_t ctx;   /* [T, H*dh]   attention output, heads concatenated */
+  size_t lse;   /* [B, H, S]   fp32 log-sum-exp of the scaled masked scores */
+  size_t x1;    /* [T, D]      x + ctx Wo + bo */
+  size_t h2;    /* [T, D]      LN2(x1) */
+  size_t u;     /* [T, F]      h2 W1 + b1 */
+  size_t a;     /* [T, F]      gelu(u) */
+  size_t mu1, rstd1, mu2, rstd2; /* [T] fp32 each */
+  size_t total; /* bytes to allocate */
+} FaxSavedLayout;
+
+/* Byte offsets of the activation gradients fax_block_bwd leaves in its
+ * workspace (valid after the call; element type dims.dtype).  Exposed so a
+ * caller or test can inspect them; not needed for normal use. */
+typedef struct FaxBwdLayout {
+  size_t du;    /* [T, F]      gradient at u */
+  size_t dh2;   /* [T, D]      du W1^T: the MLP input-gradient partial sum */
+  size_t dx1;   /* [T, D]      gradient at x1 */
+  size_t dctx;  /* [T, H*dh] */
+  size_t dqkv;  /* [T, 3*H*dh] */
+  size_t dh1;   /* [T, D]      dqkv Wqkv^T: the attention input-gradient partial sum */
+  size_t total; /* == fax_block_workspace_bytes */
+} FaxBwdLayout;
+
+typedef struct FaxAdamW {
+  float lr, beta1, beta2, eps, wd;
+} FaxAdamW;
+
+/* Full model (final LayerNorm, tied output projection, learned positions). */
+typedef struct FaxModelDims {
+  FaxBlockDims blk; /* blk.B, blk.S give the batch */
+  int32_t L;        /* layers */
+  int32_t V;        /* vocabulary */
+  int32_t S_max;    /* rows of the position table, >= blk.S */
+  uint32_t flags;
+} FaxModelDims;
+
+/* Pointer table of the model's parameters, or buffers shaped like them.
+ *   tok_emb [V, D]; pos_emb [S_max, D]; lnf_g, lnf_b [D];
+ *   blocks: HOST array of L FaxBlockTensors. */
+typedef struct FaxModelTensors {
+  void *tok_emb, *pos_emb, *lnf_g, *lnf_b;
+  const FaxBlockTensors* blocks;
+} FaxModelTensors;
+
+/* Build id; names the GPU target the kernels were compiled for ("gfx950"). */
+const char* fax_version(void);
+/* Text of the calling thread's most recent error ("" if none). */
+const char* fax_last_error(void);
+
+/* Host-only size queries. */
+int fax_block_saved_layout(const FaxBlockDims* dims, FaxSavedLayout* out);
+int fax_block_bwd_layout(const FaxBlockDims* dims, FaxBwdLayout* out);
+int fax_block_workspace_bytes(const FaxBlockDims* dims, size_t* out); /* covers fwd and bwd */
+int fax_train_workspace_bytes(const FaxModelDims* dims, size_t* out);
+
+/* Host-only argument check used by every entry point; exposed for tests. */
+int fax_block_dims_check(const FaxBlockDims* dims);
+
+/*
+ * Forward pass of one pre-LayerNorm decoder block (Fig. 1; forward phase of Fig. 4):
+ *   h1 = LN(x; ln1);  qkv = h1 Wqkv + bqkv;  ctx = causal softmax(Q K^T / sqrt(dh)) V per head;
+ *   x1 = x + ctx Wo + bo;  h2 = LN(x1; ln2);  u = h2 W1 + b1;  a = gelu(u);  y = x1 + a W2 + b2.
+ * params: tensors in dims.dtype.  x, y: [B,S,D] in dims.dtype; y must not alias x.
+ * saved: buffer of fax_block_saved_layout().total bytes, filled for fax_block_bwd.
+ * p_attn, p_mlp: with FAX_FLAG_TP_PARTIAL, [B,S,D] outputs receiving ctx Wo and a W2
+ *   (no bias, no residual): the partial sums a tensor-parallel rank holds before the
+ *   reduction over the model axis (Sec. 3.2).  Ignored (may be NULL) without the flag.
+ * ws: workspace of at least fax_block_workspace_bytes().
+ */
+int fax_block_fwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const void* x, void* y,
+                  void* saved, void* p_attn, void* p_mlp, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward pass of the same block (backward phase of Fig. 4).
+ * dy: [B,S,D] upstream gradient; x: the forward input; saved: as filled by fax_block_fwd.
+ * dx: [B,S,D] gradient at x (may alias dy).
+ * grads: twelve fp32 buffers; accumulate != 0 adds into them, 0 overwrites.
+ * After the call the workspace holds the activation gradients at the offsets of
+ * fax_block_bwd_layout(), among them the input-gradient partial sums dh1 and dh2.
+ */
+int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const void* x, const void* dy,
+                  const void* saved, void* dx, const FaxBlockTensors* grads, int accumulate,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Adam with decoupled weight decay on one tensor of n elements (Table 1 caption: Adam;
+ * wd = 0 is plain Adam), step >= 1:
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ *   p = p (1 - lr wd) - lr (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps).
+ * master, m, v: fp32, updated in place (parameters are kept in fp32, Sec. 3).
+ * grad: fp32.  lowp: optional bf16 buffer receiving the rounded new parameters (NULL to skip).
+ */
+int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp, size_t n,
+                   const FaxAdamW* hp, int step, void* stream);
+
+/*
+ * One training step of the full model (forward, loss, backward, update: Fig. 4 + Table 1):
+ *   x0 = tok_emb[tokens] + pos_emb[s];  L blocks;  hf = LN(x_L; lnf);  logits = hf tok_emb^T;
+ *   loss = mean over B*S positions of logsumexp(logits) - logits[label];
+ *   gradients of every tensor; then fax_adamw_step on every tensor unless FAX_FLAG_SKIP_UPDATE.
+ * params: compute copy in dims.blk.dtype (rewritten by the update when bf16).
+ * master, m, v: fp32 state (for FAX_F32, master may equal params: one copy, updated in place).
+ * grads: fp32, overwritten.  tokens, labels: int32 [B,S], values in [0,V) (caller validates).
+ * loss_out: one fp32 on the device.
+ */
+int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, const FaxModelTensors* master,
+                   const FaxModelTensors* m, const FaxModelTensors* v, const FaxModelTensors* grads,
+                   const int32_t* tokens, const int32_t* labels, const FaxAdamW* hp, int step,
+                   float* loss_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Building blocks, exported so each kernel can be checked and timed alone.
+ * All follow the conventions above; dtype is FAX_F32 or FAX_BF16.
+ */
+
+/* C[M,N] = op(A) op(B), fp32 accumulate.  ta = 0: A is [M,K] row-major (lda); ta = 1: A is
+ * stored [K,M].  tb = 0: B is [K,N] row-major; tb = 1: B is stored [N,K].  c_f32 != 0
+ * stores C as fp32 (and adds into it when accumulate != 0), else in dtype.
+ * bias: optional [N] in dtype; residual: optional [M,N] in dtype, added after the bias.
+ * path: 0 = choose, 1 = force the scalar-FMA kernel, 2 = force the MFMA kernel (bf16 only,
+ * FAX_ERR_UNSUPPORTED if the shape does not tile). */
+int fax_gemm(int dtype, int ta, int tb, int M, int N, int K, const void* A, int lda, const void* B,
+             int ldb, void* C, int ldc, int c_f32, int accumulate, const void* bias,
+             const void* residual, int ldr, int path, void* stream);
+
+/* h = LN(x); mu, rstd: fp32 [rows]. */
+int fax_layernorm_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const void* beta,
+                      float eps, void* h, float* mu, float* rstd, void* stream);
+/* dx = (dres ? dres : 0) + LN-backward(dh); dgamma, dbeta fp32 [D] (accumulate as above).
+ * ws: at least fax_layernorm_bwd_workspace_bytes(D). */
+int fax_layernorm_bwd(int dtype, int rows, int D, const void* dh, const void* x, const float* mu,
+                      const float* rstd, const void* gamma, const void* dres, void* dx,
+                      float* dgamma, float* dbeta, int accumulate, void* ws, size_t ws_bytes,
+                      void* stream);
+size_t fax_layernorm_bwd_workspace_bytes(int D);
+
+/* Causal attention over qkv [B,S,3*H*dh] -> ctx [B,S,H*dh], lse fp32 [B,H,S].
+ * path: 0 = choose, 1 = scalar kernel, 2 = MFMA kernel. */
+int fax_attention_fwd(int dtype, int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse,
+                      int path, void* stream);
+/* dqkv from dctx; delta: fp32 [B,H,S] scratch. */
+int fax_attention_bwd(int dtype, int B, int S, int H, int dh, const void* qkv, const void* ctx,
+                      const float* lse, const void* dctx, void* dqkv, float* delta, int path,
+                      void* stream);
+
+/* Mean softmax cross-entropy over rows of logits [N,V]; dlogits may alias logits.
+ * row_loss: fp32 [N] scratch; loss_out: one fp32. */
+int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels,
+                      void* dlogits, float* row_loss, float* loss_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAX_H */

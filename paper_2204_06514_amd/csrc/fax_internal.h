@@ -1,0 +1,183 @@
+// Internal declarations shared by the kernel files and the C-ABI layer of libfax.
+// Target: gfx950 (CDNA4) only; wavefront = 64 lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fax.h"
+
+namespace fax {
+
+typedef __bf16 bf16_t;
+
+// ---- error text for the calling thread -------------------------------------------------
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define FAX_HIP(call)                                   \
+  do {                                                  \
+    hipError_t e_ = (call);                             \
+    if (e_ != hipSuccess) return fax::hip_fail(e_, #call); \
+  } while (0)
+#define FAX_TRY(call)          \
+  do {                         \
+    int s_ = (call);           \
+    if (s_ != FAX_OK) return s_; \
+  } while (0)
+#define FAX_LAUNCH_CHECK(name) FAX_HIP(hipGetLastError())
+
+// ---- GEMM -------------------------------------------------------------------------------
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_DGELU = 2 };
+enum { PATH_AUTO = 0, PATH_SIMT = 1, PATH_MFMA = 2 };
+
+// C[M,N] = op(A) op(B) in fp32, then (in this order):
+//   C2 = acc                       (EPI_NONE with C2: the pre-bias partial product)
+//   acc += bias[n]; acc += R[m,n]
+//   EPI_GELU : C = acc, C2 = gelu(acc)
+//   EPI_DGELU: C = acc * gelu'(U[m,n])
+//   otherwise: C = acc (fp32 C may accumulate)
+struct GemmArgs {
+  int dtype = FAX_BF16;
+  bool ta = false, tb = false;
+  int M = 0, N = 0, K = 0;
+  const void* A = nullptr; int lda = 0;
+  const void* B = nullptr; int ldb = 0;
+  void* C = nullptr; int ldc = 0;
+  bool c_f32 = false, accumulate = false;
+  const void* bias = nullptr;
+  const void* R = nullptr; int ldr = 0;
+  int epi = EPI_NONE;
+  void* C2 = nullptr; int ldc2 = 0;
+  const void* U = nullptr; int ldu = 0;
+  int gelu_form = FAX_GELU_TANH;
+  int path = PATH_AUTO;
+};
+int gemm(const GemmArgs& g, hipStream_t s);
+int gemm_simt(const GemmArgs& g, hipStream_t s);
+bool gemm_mfma_supported(const GemmArgs& g);
+int gemm_mfma(const GemmArgs& g, hipStream_t s);
+
+// ---- LayerNorm, column sums ---------------------------------------------------------------
+int ln_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const void* beta, float eps,
+           void* h, float* mu, float* rstd, hipStream_t s);
+size_t ln_bwd_ws_bytes(int D);
+int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const float* mu, const float* rstd,
+           const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta, bool accumulate,
+           void* ws, hipStream_t s);
+size_t colsum_ws_bytes(int N);
+// out[n] (+)= sum over rows of a[r, n]; a in dtype with leading dimension lda.
+int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws,
+           hipStream_t s);
+
+// ---- attention ------------------------------------------------------------------------------
+int attn_fwd_simt(int dtype, int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, hipStream_t s);
+int attn_bwd_simt(int dtype, int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
+                  const void* dctx, void* dqkv, float* delta, hipStream_t s);
+bool attn_mfma_supported(int dtype, int B, int S, int H, int dh);
+int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, hipStream_t s);
+int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
+                  const void* dctx, void* dqkv, float* delta, hipStream_t s);
+
+// ---- loss, embedding, optimizer ---------------------------------------------------------------
+int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
+                  float* row_loss, float* loss_out, hipStream_t s);
+int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb,
+              void* x0, hipStream_t s);
+// g_tok[tokens[b,s]] += dx0[b,s] (fp32 atomics); g_pos[s] = sum_b dx0[b,s]; rows of g_pos beyond S untouched.
+int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
+              hipStream_t s);
+int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
+          hipStream_t s);
+int fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// ---- device helpers -----------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// 16-byte vector of T: 4 floats or 8 bf16.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
+  __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return reinterpret_cast<const float*>(&raw)[i]; }
+  __device__ __forceinline__ void set(int i, float v) { reinterpret_cast<float*>(&raw)[i] = v; }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void store(bf16_t* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const {
+    uint32_t w = reinterpret_cast<const uint32_t*>(&raw)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  __device__ __forceinline__ void set(int i, float v) { reinterpret_cast<bf16_t*>(&raw)[i] = (bf16_t)v; }
+};
+
+// GELU, both forms, and its derivative.
+__device__ __forceinline__ float gelu_f(float u, int form) {
+  if (form == FAX_GELU_TANH) {
+    float t = tanhf(0.7978845608028654f * (u + 0.044715f * u * u * u));
+    return 0.5f * u * (1.0f + t);
+  }
+  return 0.5f * u * (1.0f + erff(u * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_grad_f(float u, int form) {
+  if (form == FAX_GELU_TANH) {
+    float t = tanhf(0.7978845608028654f * (u + 0.044715f * u * u * u));
+    return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 0.134145f * u * u);
+  }
+  float cdf = 0.5f * (1.0f + erff(u * 0.7071067811865476f));
+  float pdf = 0.3989422804014327f * expf(-0.5f * u * u);
+  return cdf + u * pdf;
+}
+// ---- GEMM epilogue shared by the scalar and MFMA kernels ----
+struct EpiArgs {
+  const void* bias;
+  const void* R; int ldr;
+  void* C; int ldc;
+  void* C2; int ldc2;
+  const void* U; int ldu;
+  int epi, gelu_form, c_f32, accumulate;
+};
+
+template <typename T>
+__device__ __forceinline__ void epilogue_store(const EpiArgs& e, int m, int n, float acc) {
+  if (e.epi == EPI_NONE && e.C2) ((T*)e.C2)[(size_t)m * e.ldc2 + n] = from_f<T>(acc);
+  if (e.bias) acc += to_f(((const T*)e.bias)[n]);
+  if (e.R) acc += to_f(((const T*)e.R)[(size_t)m * e.ldr + n]);
+  if (e.epi == EPI_GELU) {
+    ((T*)e.C)[(size_t)m * e.ldc + n] = from_f<T>(acc);
+    ((T*)e.C2)[(size_t)m * e.ldc2 + n] = from_f<T>(gelu_f(acc, e.gelu_form));
+  } else {
+    if (e.epi == EPI_DGELU) acc *= gelu_grad_f(to_f(((const T*)e.U)[(size_t)m * e.ldu + n]), e.gelu_form);
+    if (e.c_f32) {
+      float* c = (float*)e.C + (size_t)m * e.ldc + n;
+      *c = e.accumulate ? *c + acc : acc;
+    } else {
+      ((T*)e.C)[(size_t)m * e.ldc + n] = from_f<T>(acc);
+    }
+  }
+}
+
+#endif  // __HIPCC__
+
+}  // namespace fax

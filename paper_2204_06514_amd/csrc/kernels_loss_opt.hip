@@ -1,0 +1,271 @@
+// HBM-bound kernels around the blocks: softmax cross-entropy (forward + gradient in one pass
+// over the logits), embedding gather / scatter, and the AdamW update.
+#include "fax_internal.h"
+
+namespace fax {
+
+// ---------------------------------------------------------------------------------------------
+// Cross-entropy.  One 1024-thread block per row; the row is read from HBM once (cached in
+// registers as raw 16-byte vectors when it fits), reduced to max and sum-exp, and the gradient
+// (softmax - onehot)/N is written over it.
+// ---------------------------------------------------------------------------------------------
+static constexpr int CE_THREADS = 1024;
+static constexpr int CE_MAXV = 8;
+
+__device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < nw; i++) r = is_max ? fmaxf(r, red[i]) : r + red[i];
+  return r;
+}
+
+template <typename T, bool CACHED>
+__global__ __launch_bounds__(CE_THREADS) void ce_kernel(int N, int V, const T* __restrict__ logits,
+                                                        const int32_t* __restrict__ labels, T* __restrict__ dlogits,
+                                                        float* __restrict__ row_loss) {
+  using Vv = Vec16<T>;
+  __shared__ float red[CE_THREADS / 64];
+  const int row = blockIdx.x;
+  const T* z = logits + (size_t)row * V;
+  T* dz = dlogits + (size_t)row * V;
+  const int nvec = V / Vv::N;  // CACHED requires V % Vv::N == 0
+  const int label = labels[row];
+  const float invN = 1.f / (float)N;
+  Vv zv[CE_MAXV];
+  float mx = -INFINITY;
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < CE_MAXV; i++) {
+      const int c = threadIdx.x + i * CE_THREADS;
+      if (c < nvec) {
+        zv[i].load(z + c * Vv::N);
+#pragma unroll
+        for (int e = 0; e < Vv::N; e++) mx = fmaxf(mx, zv[i].get(e));
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < V; c += CE_THREADS) mx = fmaxf(mx, to_f(z[c]));
+  }
+  mx = block_reduce(mx, red, true);
+  float se = 0.f;
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < CE_MAXV; i++) {
+      const int c = threadIdx.x + i * CE_THREADS;
+      if (c < nvec) {
+#pragma unroll
+        for (int e = 0; e < Vv::N; e++) se += expf(zv[i].get(e) - mx);
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < V; c += CE_THREADS) se += expf(to_f(z[c]) - mx);
+  }
+  se = block_reduce(se, red, false);
+  const float inv = invN / se;
+  if (threadIdx.x == 0) row_loss[row] = (mx + logf(se)) - to_f(z[label]);
+  __syncthreads();  // z[label] is read before anyone overwrites it (dz may alias z)
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < CE_MAXV; i++) {
+      const int c = threadIdx.x + i * CE_THREADS;
+      if (c < nvec) {
+        Vv o;
+#pragma unroll
+        for (int e = 0; e < Vv::N; e++) {
+          float g = expf(zv[i].get(e) - mx) * inv;
+          if (c * Vv::N + e == label) g -= invN;
+          o.set(e, g);
+        }
+        o.store(dz + c * Vv::N);
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < V; c += CE_THREADS) {
+      float g = expf(to_f(z[c]) - mx) * inv;
+      if (c == label) g -= invN;
+      dz[c] = from_f<T>(g);
+    }
+  }
+}
+
+// loss = mean(row_loss), summed in a fixed order by one block.
+__global__ __launch_bounds__(1024) void mean_kernel(int N, const float* __restrict__ v, float* __restrict__ out) {
+  __shared__ float red[16];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < N; i += 1024) s += v[i];
+  s = block_reduce(s, red, false);
+  if (threadIdx.x == 0) *out = s / (float)N;
+}
+
+template <typename T>
+static int ce_t(int N, int V, const T* logits, const int32_t* labels, T* dlogits, float* row_loss, float* loss_out,
+                hipStream_t s) {
+  constexpr int VN = Vec16<T>::N;
+  if (V % VN == 0 && V / VN <= CE_THREADS * CE_MAXV)
+    hipLaunchKernelGGL((ce_kernel<T, true>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss);
+  else
+    hipLaunchKernelGGL((ce_kernel<T, false>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss);
+  FAX_LAUNCH_CHECK("cross_entropy");
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, s, N, row_loss, loss_out);
+  FAX_LAUNCH_CHECK("cross_entropy_mean");
+  return FAX_OK;
+}
+
+int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                  float* loss_out, hipStream_t s) {
+  if (N == 0) return FAX_OK;
+  if (dtype == FAX_F32) return ce_t<float>(N, V, (const float*)logits, labels, (float*)dlogits, row_loss, loss_out, s);
+  return ce_t<bf16_t>(N, V, (const bf16_t*)logits, labels, (bf16_t*)dlogits, row_loss, loss_out, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Embedding
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(int S, int D, const int32_t* __restrict__ tokens,
+                                                        const T* __restrict__ tok_emb, const T* __restrict__ pos_emb,
+                                                        T* __restrict__ x0) {
+  const int t = blockIdx.x;  // token position b*S + s
+  const int s = t % S;
+  const T* e = tok_emb + (size_t)tokens[t] * D;
+  const T* p = pos_emb + (size_t)s * D;
+  T* o = x0 + (size_t)t * D;
+  for (int d = threadIdx.x; d < D; d += 256) o[d] = from_f<T>(to_f(e[d]) + to_f(p[d]));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_tok_kernel(int D, const int32_t* __restrict__ tokens,
+                                                            const T* __restrict__ dx0, float* __restrict__ g_tok) {
+  const int t = blockIdx.x;
+  float* g = g_tok + (size_t)tokens[t] * D;
+  const T* dx = dx0 + (size_t)t * D;
+  for (int d = threadIdx.x; d < D; d += 256) atomicAdd(g + d, to_f(dx[d]));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_pos_kernel(int B, int S, int D, const T* __restrict__ dx0,
+                                                            float* __restrict__ g_pos) {
+  const int s = blockIdx.x;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    float a = 0.f;
+    for (int b = 0; b < B; b++) a += to_f(dx0[((size_t)b * S + s) * D + d]);
+    g_pos[(size_t)s * D + d] = a;
+  }
+}
+
+int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb, void* x0,
+              hipStream_t s) {
+  if (B * S == 0) return FAX_OK;
+  if (dtype == FAX_F32)
+    hipLaunchKernelGGL((embed_fwd_kernel<float>), dim3(B * S), dim3(256), 0, s, S, D, tokens, (const float*)tok_emb,
+                       (const float*)pos_emb, (float*)x0);
+  else
+    hipLaunchKernelGGL((embed_fwd_kernel<bf16_t>), dim3(B * S), dim3(256), 0, s, S, D, tokens, (const bf16_t*)tok_emb,
+                       (const bf16_t*)pos_emb, (bf16_t*)x0);
+  FAX_LAUNCH_CHECK("embed_fwd");
+  return FAX_OK;
+}
+
+int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
+              hipStream_t s) {
+  if (B * S == 0) return FAX_OK;
+  if (dtype == FAX_F32) {
+    hipLaunchKernelGGL((embed_bwd_tok_kernel<float>), dim3(B * S), dim3(256), 0, s, D, tokens, (const float*)dx0, g_tok);
+    hipLaunchKernelGGL((embed_bwd_pos_kernel<float>), dim3(S), dim3(256), 0, s, B, S, D, (const float*)dx0, g_pos);
+  } else {
+    hipLaunchKernelGGL((embed_bwd_tok_kernel<bf16_t>), dim3(B * S), dim3(256), 0, s, D, tokens, (const bf16_t*)dx0, g_tok);
+    hipLaunchKernelGGL((embed_bwd_pos_kernel<bf16_t>), dim3(S), dim3(256), 0, s, B, S, D, (const bf16_t*)dx0, g_pos);
+  }
+  FAX_LAUNCH_CHECK("embed_bwd");
+  return FAX_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// AdamW: 16 B/param read (g, p, m, v) + 12 B/param written (+2 for the bf16 copy).
+// ---------------------------------------------------------------------------------------------
+struct AdamScalars {
+  float b1, b2, one_m_b1, one_m_b2, inv_bc1, inv_bc2, lr, eps, decay;
+};
+
+__device__ __forceinline__ void adam_one(float g, float& p, float& m, float& v, const AdamScalars& a) {
+  m = a.b1 * m + a.one_m_b1 * g;
+  v = a.b2 * v + a.one_m_b2 * g * g;
+  const float mh = m * a.inv_bc1;
+  const float vh = v * a.inv_bc2;
+  p = p * a.decay - a.lr * mh / (sqrtf(vh) + a.eps);
+}
+
+__global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict__ p, float* __restrict__ m,
+                                                    float* __restrict__ v, const float* __restrict__ g,
+                                                    bf16_t* __restrict__ lowp, AdamScalars a) {
+  const size_t nvec = n / 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    float4 pv = reinterpret_cast<float4*>(p)[i], mv = reinterpret_cast<float4*>(m)[i];
+    float4 vv = reinterpret_cast<float4*>(v)[i];
+    const float4 gv = reinterpret_cast<const float4*>(g)[i];
+    adam_one(gv.x, pv.x, mv.x, vv.x, a);
+    adam_one(gv.y, pv.y, mv.y, vv.y, a);
+    adam_one(gv.z, pv.z, mv.z, vv.z, a);
+    adam_one(gv.w, pv.w, mv.w, vv.w, a);
+    reinterpret_cast<float4*>(p)[i] = pv;
+    reinterpret_cast<float4*>(m)[i] = mv;
+    reinterpret_cast<float4*>(v)[i] = vv;
+    if (lowp) {
+      union { bf16_t h[4]; uint2 u; } pk;
+      pk.h[0] = (bf16_t)pv.x; pk.h[1] = (bf16_t)pv.y; pk.h[2] = (bf16_t)pv.z; pk.h[3] = (bf16_t)pv.w;
+      reinterpret_cast<uint2*>(lowp)[i] = pk.u;
+    }
+  }
+  // ragged tail
+  for (size_t i = nvec * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    float pp = p[i], mm = m[i], vv = v[i];
+    adam_one(g[i], pp, mm, vv, a);
+    p[i] = pp; m[i] = mm; v[i] = vv;
+    if (lowp) lowp[i] = (bf16_t)pp;
+  }
+}
+
+int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
+          hipStream_t s) {
+  if (n == 0) return FAX_OK;
+  AdamScalars a;
+  a.b1 = hp.beta1; a.b2 = hp.beta2;
+  a.one_m_b1 = 1.f - hp.beta1; a.one_m_b2 = 1.f - hp.beta2;
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)hp.beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)hp.beta2, (double)step)));
+  a.lr = hp.lr; a.eps = hp.eps;
+  a.decay = 1.f - hp.lr * hp.wd;
+  size_t blocks = (n / 4 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, grad, (bf16_t*)lowp, a);
+  FAX_LAUNCH_CHECK("adamw");
+  return FAX_OK;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, size_t nvec, size_t bytes) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (size_t i = first; i < nvec; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+  unsigned char* tail = reinterpret_cast<unsigned char*>(p);
+  for (size_t i = nvec * 16 + first; i < bytes; i += stride) tail[i] = 0;
+}
+
+// p must be 16-byte aligned; any byte count.
+int fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return FAX_OK;
+  size_t nvec = bytes / 16;
+  size_t blocks = (nvec + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, nvec, bytes);
+  FAX_LAUNCH_CHECK("fill_zero");
+  return FAX_OK;
+}
+
+}  // namespace fax

@@ -1,0 +1,85 @@
+"""End-to-end parity of fax_block_fwd / fax_block_bwd against the CPU oracle, through the C ABI.
+
+Bar: fp32 workloads, max-norm relative error <= 1e-5 per tensor; bf16 workloads, Frobenius-norm
+relative error <= 2e-2 per output and gradient tensor.  Both sides receive the same seeded inputs,
+already rounded to the storage precision.
+"""
+import numpy as np
+import pytest
+
+from oracle import transformer as orc
+from workloads import BlockShape, get_config, make_block_inputs, PARAM_NAMES
+from helpers import run_block, err, tol, rel_max
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_block(sh, out, p, x, dy, gelu, partial=False):
+    y, c = orc.block_fwd(x, p, sh.H, sh.dh, gelu, sh.ln_eps)
+    dx, g, it = orc.block_bwd(dy, c, p)
+    t = tol(sh.dtype)
+    report = {"y": err(out["y"], y, sh.dtype), "dx": err(out["dx"], dx, sh.dtype)}
+    for k in PARAM_NAMES:
+        report["d" + k] = err(out["grads"][k], g[k], sh.dtype)
+    flat = lambda a: a.reshape(-1, a.shape[-1])
+    for k in ("h1", "qkv", "ctx", "x1", "h2", "u", "a"):
+        report["saved." + k] = err(out["saved"][k], flat(c[k]), sh.dtype)
+    for k in ("du", "dh2", "dx1", "dctx", "dqkv", "dh1"):
+        report["bwd." + k] = err(out["bwd"][k], flat(it[k]), sh.dtype)
+    if partial:
+        report["p_attn"] = err(out["p_attn"], c["p_attn"], sh.dtype)
+        report["p_mlp"] = err(out["p_mlp"], c["p_mlp"], sh.dtype)
+    bad = {k: v for k, v in report.items() if not v <= t}
+    assert not bad, (bad, report)
+    # the key-bias gradient is analytically zero: a free check on the attention backward
+    Hd = sh.Hd
+    gb = out["grads"]["bqkv"]
+    assert np.abs(gb[Hd:2 * Hd]).max() <= (1e-5 if sh.dtype == "f32" else 2e-2) * np.abs(gb).max()
+    return report
+
+
+@pytest.mark.parametrize("gelu", ["tanh", "erf"])
+@pytest.mark.parametrize("generic", [False, True])
+def test_cfg1_fp32_block(gelu, generic):
+    sh = get_config("cfg1")
+    p, x, dy = make_block_inputs(sh, seed=0, generic=generic)
+    out = run_block(sh, p, x, dy, gelu=gelu)
+    _check_block(sh, out, p, x, dy, gelu)
+
+
+def test_fp32_ragged_shapes_and_partial_sums():
+    sh = BlockShape(B=3, S=37, D=72, H=3, dh=20, F=100, dtype="f32", sigma_w=0.05)
+    p, x, dy = make_block_inputs(sh, seed=4, generic=True)
+    out = run_block(sh, p, x, dy, partial=True)
+    _check_block(sh, out, p, x, dy, "tanh", partial=True)
+
+
+def test_gradient_accumulation_flag():
+    sh = get_config("cfg1")
+    p, x, dy = make_block_inputs(sh, seed=1, generic=True)
+    rng = np.random.default_rng(0)
+    init = {k: rng.standard_normal(p[k].shape) for k in PARAM_NAMES}
+    out = run_block(sh, p, x, dy, accumulate=True, grads_init=init)
+    _, c = orc.block_fwd(x, p, sh.H, sh.dh)
+    _, g, _ = orc.block_bwd(dy, c, p)
+    for k in PARAM_NAMES:
+        ref = init[k].astype(np.float32).astype(np.float64) + g[k]
+        assert rel_max(out["grads"][k], ref) <= 1e-5, k
+
+
+BF16_SMALL = [
+    # several MFMA tiles in every GEMM
+    BlockShape(B=2, S=256, D=256, H=4, dh=64, F=1024, dtype="bf16", sigma_w=0.02),
+    # a tensor-parallel share: H*dh != D
+    BlockShape(B=1, S=384, D=512, H=2, dh=128, F=256, dtype="bf16", sigma_w=0.02),
+    # ragged everything: the scalar fallback kernels
+    BlockShape(B=2, S=100, D=136, H=3, dh=24, F=200, dtype="bf16", sigma_w=0.05),
+]
+
+
+@pytest.mark.parametrize("sh", BF16_SMALL, ids=lambda s: "D%d_S%d_dh%d" % (s.D, s.S, s.dh))
+@pytest.mark.parametrize("generic", [False, True])
+def test_bf16_small_blocks(sh, generic):
+    p, x, dy = make_block_inputs(sh, seed=2, generic=generic)
+    out = run_block(sh, p, x, dy, partial=True)
+    _check_block(sh, out, p, x, dy, "tanh", partial=True)

@@ -1,0 +1,175 @@
+"""Per-kernel parity on the GPU against the CPU oracle (or, for a bare GEMM, the float64 product
+that the oracle's own matmul step is), through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2204_06514_amd as fax
+from oracle import transformer as orc
+from workloads import round_to_bf16
+from helpers import DEV, TDTYPE, CODE, to_dev, to_np, err, tol, rel_max, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def _store(a, dtype):
+    return round_to_bf16(a) if dtype == "bf16" else a.astype(np.float32).astype(np.float64)
+
+
+# ------------------------------------------------------------------------------ GEMM
+GEMM_CASES = [
+    # dtype, path, ta, tb, M, N, K
+    ("f32", fax.PATH_SCALAR, 0, 0, 128, 384, 128),
+    ("f32", fax.PATH_SCALAR, 0, 1, 70, 33, 19),
+    ("f32", fax.PATH_SCALAR, 1, 0, 65, 130, 257),
+    ("f32", fax.PATH_SCALAR, 1, 1, 5, 7, 3),
+    ("bf16", fax.PATH_SCALAR, 0, 0, 100, 72, 40),
+    ("bf16", fax.PATH_SCALAR, 1, 0, 96, 40, 200),
+    ("bf16", fax.PATH_MFMA, 0, 0, 256, 384, 192),     # 128-tiles, forward form
+    ("bf16", fax.PATH_MFMA, 0, 1, 384, 128, 256),     # input-gradient form
+    ("bf16", fax.PATH_MFMA, 1, 0, 128, 256, 320),     # weight-gradient form
+    ("bf16", fax.PATH_MFMA, 1, 1, 128, 128, 64),
+    ("bf16", fax.PATH_MFMA, 0, 0, 2048, 4096, 256),   # 256-tiles
+    ("bf16", fax.PATH_MFMA, 0, 1, 4096, 2048, 128),
+    ("bf16", fax.PATH_MFMA, 1, 0, 2048, 4096, 192),
+    ("bf16", fax.PATH_MFMA, 1, 1, 4096, 2048, 64),
+]
+
+
+@pytest.mark.parametrize("dtype,path,ta,tb,M,N,K", GEMM_CASES)
+def test_gemm_all_orientations(dtype, path, ta, tb, M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A = _store(rng.standard_normal((K, M) if ta else (M, K)), dtype)
+    B = _store(rng.standard_normal((N, K) if tb else (K, N)), dtype)
+    bias = _store(rng.standard_normal(N), dtype)
+    R = _store(rng.standard_normal((M, N)), dtype)
+    ref = (A.T if ta else A) @ (B.T if tb else B)
+    Ad, Bd, bd, Rd = (to_dev(a, dtype) for a in (A, B, bias, R))
+    Cd = torch.empty((M, N), dtype=TDTYPE[dtype], device=DEV)
+    fax.fax_gemm(CODE[dtype], ta, tb, M, N, K, Ad, A.shape[1], Bd, B.shape[1], Cd, N, bias=bd, residual=Rd, ldr=N,
+                 path=path)
+    assert err(to_np(Cd), ref + bias + R, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+    # fp32 output, overwrite then accumulate
+    Cf = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
+    fax.fax_gemm(CODE[dtype], ta, tb, M, N, K, Ad, A.shape[1], Bd, B.shape[1], Cf, N, c_f32=1, path=path)
+    assert rel_max(to_np(Cf), ref) <= 1e-5
+    fax.fax_gemm(CODE[dtype], ta, tb, M, N, K, Ad, A.shape[1], Bd, B.shape[1], Cf, N, c_f32=1, accumulate=1, path=path)
+    assert rel_max(to_np(Cf), 2 * ref) <= 1e-5
+
+
+def test_gemm_auto_path_falls_back_on_ragged_shapes():
+    rng = np.random.default_rng(0)
+    M, N, K = 130, 136, 72
+    A = round_to_bf16(rng.standard_normal((M, K))); B = round_to_bf16(rng.standard_normal((K, N)))
+    Cd = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    fax.fax_gemm(fax.FAX_BF16, 0, 0, M, N, K, to_dev(A, "bf16"), K, to_dev(B, "bf16"), N, Cd, N)
+    assert rel_fro(to_np(Cd), A @ B) <= 4e-3
+    with pytest.raises(fax.FaxError):
+        fax.fax_gemm(fax.FAX_BF16, 0, 0, M, N, K, to_dev(A, "bf16"), K, to_dev(B, "bf16"), N, Cd, N, path=fax.PATH_MFMA)
+
+
+# ------------------------------------------------------------------------- LayerNorm
+@pytest.mark.parametrize("dtype,rows,D", [("f32", 128, 128), ("f32", 37, 100), ("f32", 9, 4096), ("bf16", 300, 1024),
+                                          ("bf16", 129, 4096), ("bf16", 33, 12288), ("bf16", 21, 1000),
+                                          ("bf16", 17, 20000)])
+def test_layernorm_forward_backward(dtype, rows, D):
+    rng = np.random.default_rng(rows + D)
+    x = _store(rng.standard_normal((rows, D)) * 2 + 0.5, dtype)
+    g = _store(1 + 0.1 * rng.standard_normal(D), dtype); b = _store(0.1 * rng.standard_normal(D), dtype)
+    dh = _store(rng.standard_normal((rows, D)), dtype); dres = _store(rng.standard_normal((rows, D)), dtype)
+    h_ref, xhat, rstd = orc.layernorm_fwd(x, g, b, 1e-5)
+    dx_ref, dg_ref, db_ref = orc.layernorm_bwd(dh, xhat, rstd, g)
+    td = TDTYPE[dtype]
+    xd, gd, bd, dhd, drd = (to_dev(a, dtype) for a in (x, g, b, dh, dres))
+    h = torch.empty_like(xd); mu = torch.empty(rows, device=DEV); rs = torch.empty(rows, device=DEV)
+    fax.fax_layernorm_fwd(CODE[dtype], rows, D, xd, gd, bd, 1e-5, h, mu, rs)
+    assert err(to_np(h), h_ref, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+    assert rel_max(to_np(mu), x.mean(-1)) <= 1e-5 and rel_max(to_np(rs), rstd[:, 0]) <= 1e-5
+    wsb = fax.fax_layernorm_bwd_workspace_bytes(D)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    dx = torch.empty_like(xd); dg = torch.full((D,), 1.0, device=DEV); db = torch.full((D,), 1.0, device=DEV)
+    fax.fax_layernorm_bwd(CODE[dtype], rows, D, dhd, xd, mu, rs, gd, drd, dx, dg, db, 0, ws, wsb)
+    assert err(to_np(dx), dx_ref + dres, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+    assert rel_max(to_np(dg), dg_ref) <= 2e-5 and rel_max(to_np(db), db_ref) <= 2e-5
+    fax.fax_layernorm_bwd(CODE[dtype], rows, D, dhd, xd, mu, rs, gd, None, dx, dg, db, 1, ws, wsb)
+    assert err(to_np(dx), dx_ref, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+    assert rel_max(to_np(dg), 2 * dg_ref) <= 2e-5 and rel_max(to_np(db), 2 * db_ref) <= 2e-5
+
+
+# ------------------------------------------------------------------------- attention
+def _attention_case(dtype, B, S, H, dh, path, scale=1.0):
+    rng = np.random.default_rng(S * 3 + dh)
+    Hd = H * dh
+    qkv = _store(rng.standard_normal((B, S, 3 * Hd)) * scale, dtype)
+    dctx = _store(rng.standard_normal((B, S, Hd)), dtype)
+    ctx_ref, lse_ref = orc.attention_fwd(qkv, H, dh)
+    dqkv_ref = orc.attention_bwd(dctx, qkv, H, dh)
+    td = TDTYPE[dtype]
+    qd, dd = to_dev(qkv, dtype), to_dev(dctx, dtype)
+    ctx = torch.empty((B, S, Hd), dtype=td, device=DEV); lse = torch.empty((B, H, S), device=DEV)
+    fax.fax_attention_fwd(CODE[dtype], B, S, H, dh, qd, ctx, lse, path)
+    e_ctx = err(to_np(ctx), ctx_ref, dtype); e_lse = np.abs(to_np(lse) - lse_ref).max()
+    dq = torch.empty_like(qd); delta = torch.empty((B, H, S), device=DEV)
+    fax.fax_attention_bwd(CODE[dtype], B, S, H, dh, qd, ctx, lse, dd, dq, delta, path)
+    got = to_np(dq)
+    errs = [err(got[..., i * Hd:(i + 1) * Hd], dqkv_ref[..., i * Hd:(i + 1) * Hd], dtype) for i in range(3)]
+    return e_ctx, e_lse, errs
+
+
+@pytest.mark.parametrize("dtype,B,S,H,dh", [("f32", 2, 64, 4, 32), ("f32", 1, 131, 2, 48), ("f32", 1, 1, 1, 8),
+                                            ("bf16", 2, 200, 3, 64), ("bf16", 1, 70, 2, 128)])
+def test_attention_scalar_path(dtype, B, S, H, dh):
+    e_ctx, e_lse, errs = _attention_case(dtype, B, S, H, dh, fax.PATH_SCALAR)
+    t = 1e-5 if dtype == "f32" else 6e-3
+    assert e_ctx <= t and e_lse <= (2e-5 if dtype == "f32" else 1e-4) and max(errs) <= t, (e_ctx, e_lse, errs)
+
+
+# --------------------------------------------------------------------- cross-entropy
+@pytest.mark.parametrize("dtype,N,V", [("f32", 64, 1000), ("f32", 7, 37), ("bf16", 50, 51200), ("bf16", 33, 777),
+                                       ("bf16", 3, 70000)])
+def test_cross_entropy(dtype, N, V):
+    rng = np.random.default_rng(N + V)
+    z = _store(rng.standard_normal((N, V)) * 3, dtype)
+    y = rng.integers(0, V, N).astype(np.int32)
+    y[0] = 0; y[-1] = V - 1
+    loss_ref, dz_ref = orc.cross_entropy(z, y.astype(np.int64))
+    zd = to_dev(z, dtype); yd = torch.from_numpy(y).to(DEV)
+    rl = torch.empty(N, device=DEV); loss = torch.empty(1, device=DEV)
+    fax.fax_cross_entropy(CODE[dtype], N, V, zd, yd, zd, rl, loss)     # gradient written in place
+    assert abs(loss.item() - loss_ref) <= 2e-6 * abs(loss_ref)
+    assert err(to_np(zd), dz_ref, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+
+
+def test_cross_entropy_uniform_logits_give_log_vocab():
+    N, V = 5, 51200
+    zd = torch.full((N, V), 0.75, dtype=torch.bfloat16, device=DEV)
+    yd = torch.arange(N, dtype=torch.int32, device=DEV)
+    rl = torch.empty(N, device=DEV); loss = torch.empty(1, device=DEV)
+    fax.fax_cross_entropy(fax.FAX_BF16, N, V, zd, yd, zd, rl, loss)
+    assert abs(loss.item() - math.log(V)) < 1e-5
+
+
+# ----------------------------------------------------------------------------- AdamW
+@pytest.mark.parametrize("n", [1, 4099, 1 << 20])
+def test_adamw_three_steps_and_bf16_copy(n):
+    rng = np.random.default_rng(n)
+    p = rng.standard_normal(n).astype(np.float32).astype(np.float64)
+    m = np.zeros(n); v = np.zeros(n)
+    pd = to_dev(p, "f32"); md = torch.zeros(n, device=DEV); vd = torch.zeros(n, device=DEV)
+    low = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    hp = fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.01)
+    for t in range(1, 4):
+        g = (rng.standard_normal(n) * 10 ** rng.uniform(-3, 1, n)).astype(np.float32).astype(np.float64)
+        p, m, v = orc.adamw(p, m, v, g, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
+        fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), low, n, hp, t)
+        assert rel_max(to_np(pd), p) <= 1e-6
+        assert rel_max(to_np(md), m) <= 1e-6 and rel_max(to_np(vd), v) <= 1e-6
+        assert torch.equal(low, pd.to(torch.bfloat16))
+    # closed form of the first step from zero moments
+    g = rng.standard_normal(n).astype(np.float32).astype(np.float64)
+    p0 = to_np(pd)
+    md.zero_(); vd.zero_()
+    fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), None, n, hp, 1)
+    assert rel_max(to_np(pd), p0 * (1 - 1e-5) - 1e-3 * g / (np.abs(g) + 1e-8)) <= 1e-6

@@ -1,0 +1,103 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, validates
+arguments before touching the GPU, and reports consistent buffer layouts."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2204_06514_amd as fax
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fax.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fax_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert {"fax_block_fwd", "fax_block_bwd", "fax_adamw_step", "fax_train_step"} <= set(names)
+    lib = C.CDLL(fax.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(fax.EXPORTS), set(names) ^ set(fax.EXPORTS)
+
+
+def test_version_names_the_target():
+    assert "gfx950" in fax.fax_version()
+
+
+def _dims(**kw):
+    base = dict(B=2, S=64, D=128, H=4, dh=32, F=512, dtype=fax.FAX_F32)
+    base.update(kw)
+    return fax.block_dims(**base)
+
+
+def test_dims_validation():
+    assert fax.fax_block_dims_check(_dims()) == fax.FAX_OK
+    assert fax.fax_block_dims_check(_dims(B=0)) == fax.FAX_ERR_INVALID_ARG
+    assert "non-positive" in fax.fax_last_error()
+    assert fax.fax_block_dims_check(_dims(dtype=7)) == fax.FAX_ERR_INVALID_ARG
+    assert fax.fax_block_dims_check(_dims(gelu=3)) == fax.FAX_ERR_INVALID_ARG
+    assert fax.fax_block_dims_check(_dims(dh=512)) == fax.FAX_ERR_UNSUPPORTED
+    assert fax.fax_block_dims_check(_dims(H=3, dh=32)) == fax.FAX_OK      # H*dh need not equal D
+
+
+def test_saved_layout_is_disjoint_and_sized():
+    d = _dims(dtype=fax.FAX_BF16)
+    lay = fax.fax_block_saved_layout(d)
+    T, D, Hd, F = 128, 128, 128, 512
+    sizes = {"h1": T * D * 2, "qkv": T * 3 * Hd * 2, "ctx": T * Hd * 2, "lse": 2 * 4 * 64 * 4, "x1": T * D * 2,
+             "h2": T * D * 2, "u": T * F * 2, "a": T * F * 2, "mu1": T * 4, "rstd1": T * 4, "mu2": T * 4, "rstd2": T * 4}
+    spans = sorted((getattr(lay, k), getattr(lay, k) + n) for k, n in sizes.items())
+    for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+        assert a1 <= b0
+    assert spans[-1][1] <= lay.total
+    assert all(s % 256 == 0 for s, _ in spans)
+    bl = fax.fax_block_bwd_layout(d)
+    assert bl.total == fax.fax_block_workspace_bytes(d)
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
+    d = _dims()
+    good = {n: 4096 for n in fax.TENSOR_NAMES}
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_block_fwd(d, dict(good, wo=None), 4096, 8192, 4096, stream=0)
+    assert e.value.status == fax.FAX_ERR_INVALID_ARG and "params.wo" in str(e.value)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_block_fwd(d, good, 4096 + 4, 8192, 4096, stream=0)
+    assert "aligned" in str(e.value)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_block_fwd(d, good, 4096, 4096, 4096, stream=0)
+    assert "alias" in str(e.value)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_block_bwd(d, good, 4096, 4096, 4096, 4096, good, 0, 4096, 16, stream=0)
+    assert e.value.status == fax.FAX_ERR_WORKSPACE
+
+
+def test_adamw_and_train_argument_checks():
+    hp = fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.01)
+    with pytest.raises(fax.FaxError):
+        fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, hp, 0, stream=0)       # step < 1
+    with pytest.raises(fax.FaxError):
+        fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, fax.FaxAdamW(1e-3, 1.0, 0.999, 1e-8, 0.0), 1, stream=0)
+    fax.fax_adamw_step(None, None, None, None, None, 0, hp, 1, stream=0)            # n = 0 is a no-op
+    md = fax.FaxModelDims(_dims(), 2, 100, 32, 0)                                   # S_max < S
+    with pytest.raises(fax.FaxError):
+        fax.fax_train_workspace_bytes(md)
+    md = fax.FaxModelDims(_dims(), 2, 100, 64, 0)
+    assert fax.fax_train_workspace_bytes(md) > 0
+
+
+def test_gemm_argument_checks():
+    with pytest.raises(fax.FaxError):
+        fax.fax_gemm(fax.FAX_F32, 0, 0, 8, 8, 8, 4096, 4, 4096, 8, 4096, 8, stream=0)   # lda < K
+    with pytest.raises(fax.FaxError):
+        fax.fax_gemm(fax.FAX_BF16, 0, 0, 8, 8, 8, 4096, 8, 4096, 8, 4096, 8, accumulate=1, stream=0)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_gemm(fax.FAX_F32, 0, 0, 128, 128, 64, 4096, 64, 4096, 128, 4096, 128, path=fax.PATH_MFMA, stream=0)
+    assert e.value.status == fax.FAX_ERR_UNSUPPORTED
+    fax.fax_gemm(fax.FAX_F32, 0, 0, 0, 8, 8, None, 8, None, 8, None, 8, stream=0)       # empty is a no-op
