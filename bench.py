@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Throughput of the per-device Transformer training step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input, with every
+input already resident in HBM: block forward + backward (cfg3, cfg4), the same over a 2-layer
+stack plus AdamW (cfg2), or the full fax_train_step (cfg5).  Default workload: cfg3, the
+d_model=4096 block the throughput target is quoted on.
+
+Prints ONE JSON line: tokens/s (whole job = this one GPU), model TFLOP/s and its fraction of the
+bf16 MFMA peak, the roofline of the kernel that takes the most time (measured with HIP events on
+the launch stream inside the library, see fax_timing_enable), and the CPU oracle timed on a
+bounded sample of the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 flop/clk/CU, dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are built). "
+              "Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2204_06514_amd as fax
+    from workloads import get_config, make_block_inputs, make_stack_inputs, make_model_inputs, PARAM_NAMES
+    from workloads.configs import ADAMW_DEFAULT, ModelShape
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = get_config(args.config)
+    is_model = isinstance(cfg, ModelShape)
+    sh = cfg.blk if is_model else cfg
+    td = torch.bfloat16
+    code = fax.FAX_BF16
+
+    def up(a, dtype=td):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(dtype).contiguous()
+
+    dims = fax.block_dims(sh.B, sh.S, sh.D, sh.H, sh.dh, sh.F, code, fax.FAX_GELU_TANH, sh.ln_eps,
+                          fax.FAX_FLAG_TP_PARTIAL if args.config == "cfg4" else 0)
+    hp = fax.FaxAdamW(**ADAMW_DEFAULT)
+    T = sh.T
+
+    if is_model:
+        p, tok, lab = make_model_inputs(cfg, seed=0)
+        top = ("tok_emb", "pos_emb", "lnf_g", "lnf_b")
+        params = {k: up(p[k]) for k in top}
+        params["blocks"] = [{k: up(bp[k]) for k in PARAM_NAMES} for bp in p["blocks"]]
+
+        def like(fn):
+            d = {k: fn(params[k]) for k in top}
+            d["blocks"] = [{k: fn(b[k]) for k in PARAM_NAMES} for b in params["blocks"]]
+            return d
+        master = like(lambda t: t.float().clone())
+        m = like(lambda t: torch.zeros(t.shape, dtype=torch.float32, device=dev))
+        v = like(lambda t: torch.zeros(t.shape, dtype=torch.float32, device=dev))
+        grads = like(lambda t: torch.empty(t.shape, dtype=torch.float32, device=dev))
+        md = fax.FaxModelDims(dims, sh.L, cfg.V, cfg.S_max, 0)
+        wsb = fax.fax_train_workspace_bytes(md)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        tokd, labd = torch.from_numpy(tok).to(dev), torch.from_numpy(lab).to(dev)
+        loss = torch.zeros(4, device=dev)
+        tabs = [fax.model_tensors(t) for t in (params, master, m, v, grads)]
+        state = {"t": 0}
+
+        def step():
+            state["t"] += 1
+            fax.fax_train_step(md, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tokd, labd, hp, state["t"], loss, ws, wsb)
+        flops = cfg.flops_fwd_bwd(True)
+        flops_full = cfg.flops_fwd_bwd(False)
+        what = "fax_train_step: embedding + %d blocks + final LN + tied head + CE + backward + AdamW" % sh.L
+    else:
+        ps, x, dy = make_stack_inputs(sh, seed=0)
+        pd = [{k: up(p[k]) for k in PARAM_NAMES} for p in ps]
+        xs = [up(x)] + [torch.empty((sh.B, sh.S, sh.D), dtype=td, device=dev) for _ in range(sh.L)]
+        dyd = up(dy)
+        dcur = torch.empty_like(dyd)
+        lay = fax.fax_block_saved_layout(dims)
+        saved = [torch.empty(lay.total, dtype=torch.uint8, device=dev) for _ in range(sh.L)]
+        wsb = fax.fax_block_workspace_bytes(dims)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        gd = [{k: torch.empty(t.shape, dtype=torch.float32, device=dev) for k, t in p.items()} for p in pd]
+        pa = torch.empty_like(dyd) if args.config == "cfg4" else None
+        pm = torch.empty_like(dyd) if args.config == "cfg4" else None
+        with_adam = args.config == "cfg2"
+        if with_adam:
+            master = [{k: t.float().clone() for k, t in p.items()} for p in pd]
+            mo = [{k: torch.zeros_like(t) for k, t in p.items()} for p in master]
+            vo = [{k: torch.zeros_like(t) for k, t in p.items()} for p in master]
+        pt = [fax.block_tensors(p) for p in pd]
+        gt = [fax.block_tensors(g) for g in gd]
+        state = {"t": 0}
+
+        def step():
+            for l in range(sh.L):
+                fax.fax_block_fwd(dims, pt[l], xs[l], xs[l + 1], saved[l], pa, pm, ws, wsb)
+            for l in reversed(range(sh.L)):
+                fax.fax_block_bwd(dims, pt[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gt[l], 0, ws, wsb)
+            if with_adam:
+                state["t"] += 1
+                for l in range(sh.L):
+                    for k in PARAM_NAMES:
+                        fax.fax_adamw_step(master[l][k], mo[l][k], vo[l][k], gd[l][k], pd[l][k], master[l][k].numel(),
+                                           hp, state["t"])
+        flops = sh.L * sh.block_flops_fwd_bwd(True)
+        flops_full = sh.L * sh.block_flops_fwd_bwd(False)
+        what = "%d x (fax_block_fwd + fax_block_bwd)%s" % (sh.L, " + fax_adamw_step on every tensor" if with_adam else "")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # second timed region with per-kernel HIP events on the launch stream
+    fax.fax_timing_enable(1)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    rows = fax.fax_timing_report(64)
+    fax.fax_timing_enable(0)
+    rows.sort(key=lambda r: -r["ms"])
+    dom = rows[0]
+    if dom["unit"] == 0:
+        ach = dom["work"] / (dom["ms"] * 1e-3) / 1e12
+        roof = {"kernel": dom["name"], "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "launches_per_step": dom["launches"] // args.steps,
+                "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
+                "flop_per_launch_avg": dom["work"] / dom["launches"]}
+    else:
+        ach = dom["work"] / (dom["ms"] * 1e-3) / 1e9
+        roof = {"kernel": dom["name"], "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches_per_step": dom["launches"] // args.steps,
+                "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
+                "bytes_per_launch_avg": dom["work"] / dom["launches"]}
+    kernels = []
+    for r in rows:
+        per_step_ms = r["ms"] / args.steps
+        rate = r["work"] / (r["ms"] * 1e-3) if r["ms"] > 0 else 0.0
+        kernels.append({"name": r["name"], "launches_per_step": r["launches"] // args.steps,
+                        "ms_per_step": round(per_step_ms, 4),
+                        ("tflops" if r["unit"] == 0 else "gbs"): round(rate / (1e12 if r["unit"] == 0 else 1e9), 2)})
+    if args.kernels:
+        for k in kernels:
+            print(json.dumps(k), file=sys.stderr)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(args.config, cfg)
+
+    tflops = flops / dt / 1e12
+    out = {
+        "metric": "tokens_per_sec", "value": round(T / dt, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s; B=%d S=%d D=%d H=%dx%d F=%d L=%d%s" % (
+            args.config, what, sh.B, sh.S, sh.D, sh.H, sh.dh, sh.F, sh.L, (" V=%d" % cfg.V) if is_model else "")},
+        "model_tflops": round(tflops, 2), "mfma_peak_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "model_tflops_unhalved_attention": round(flops_full / dt / 1e12, 2),
+        "model_flop_per_step": flops,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(name, cfg):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample."""
+    from oracle import transformer as orc
+    from workloads import make_block_inputs, make_model_inputs
+    from workloads.configs import ModelShape
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    if isinstance(cfg, ModelShape):
+        small = cfg.scaled(B=1, S=512, L=2, V=8192, S_max=512)
+        p, tok, lab = make_model_inputs(small, seed=0)
+        t0 = time.perf_counter()
+        orc.model_loss_and_grads(p, tok, lab, small.blk.H, small.blk.dh)
+        dt = time.perf_counter() - t0
+        toks = small.blk.T
+        sample = "oracle loss+gradients of the same model cut to B=1, S=512, L=2, V=8192 (float64), one run"
+    else:
+        S = min(cfg.S, 1024 if name == "cfg4" else 2048)
+        small = cfg.scaled(B=1, S=S, L=1)
+        p, x, dy = make_block_inputs(small, seed=0)
+        t0 = time.perf_counter()
+        _, c = orc.block_fwd(x, p, small.H, small.dh)
+        orc.block_bwd(dy, c, p)
+        dt = time.perf_counter() - t0
+        toks = small.T
+        sample = "oracle block forward+backward on one batch row (B=1, S=%d) of the same block (float64), one run" % S
+    return {"value": round(toks / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle", "sample": sample,
+            "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    main()

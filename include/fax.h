@@ -104,8 +104,10 @@ typedef struct FaxBwdLayout {
   size_t total; /* == fax_block_workspace_bytes */
 } FaxBwdLayout;
 
+/* Hyper-parameters are doubles so that 1 - beta2 and the bias corrections are formed
+ * from the intended decimal values and rounded to fp32 once. */
 typedef struct FaxAdamW {
-  float lr, beta1, beta2, eps, wd;
+  double lr, beta1, beta2, eps, wd;
 } FaxAdamW;
 
 /* Full model (final LayerNorm, tied output projection, learned positions). */
@@ -230,6 +232,27 @@ int fax_attention_bwd(int dtype, int B, int S, int H, int dh, const void* qkv, c
  * row_loss: fp32 [N] scratch; loss_out: one fp32. */
 int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels,
                       void* dlogits, float* row_loss, float* loss_out, void* stream);
+
+/*
+ * Per-kernel timing with HIP events on the caller's stream: the split of a step into its
+ * phases that Fig. 4 reports, at kernel granularity.  Off by default (no events recorded).
+ * fax_timing_enable(1) clears earlier records and starts recording a start/stop event pair
+ * around every kernel family launched by any entry point of this process; (0) stops.
+ * fax_timing_report synchronises the recorded events and writes up to `capacity` rows (HOST
+ * memory), one per kernel variant: launches, summed milliseconds, and summed algorithmic work
+ * (unit 0: floating-point operations, 2 M N K per GEMM and 4 B H S^2 dh / 2 per causal
+ * attention product set; unit 1: bytes that must cross HBM).  *count receives the rows written.
+ * Process-wide state behind a mutex; meant for benchmarks, not for concurrent callers.
+ */
+typedef struct FaxKernelTime {
+  char name[64];
+  int32_t launches;
+  int32_t unit;
+  double ms;
+  double work;
+} FaxKernelTime;
+int fax_timing_enable(int on);
+int fax_timing_report(FaxKernelTime* out, int capacity, int* count);
 
 #ifdef __cplusplus
 }

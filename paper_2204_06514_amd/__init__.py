@@ -51,7 +51,7 @@ class FaxBwdLayout(C.Structure):
 
 
 class FaxAdamW(C.Structure):
-    _fields_ = [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps", "wd")]
+    _fields_ = [(n, C.c_double) for n in ("lr", "beta1", "beta2", "eps", "wd")]
 
 
 class FaxModelDims(C.Structure):
@@ -62,6 +62,11 @@ class FaxModelDims(C.Structure):
 class FaxModelTensors(C.Structure):
     _fields_ = [("tok_emb", C.c_void_p), ("pos_emb", C.c_void_p), ("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p),
                 ("blocks", C.POINTER(FaxBlockTensors))]
+
+
+class FaxKernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("launches", C.c_int32), ("unit", C.c_int32), ("ms", C.c_double),
+                ("work", C.c_double)]
 
 
 def _load():
@@ -92,6 +97,8 @@ def _load():
         "fax_attention_fwd": (i32, [i32] * 5 + [vp, vp, vp, i32, vp]),
         "fax_attention_bwd": (i32, [i32] * 5 + [vp, vp, vp, vp, vp, vp, i32, vp]),
         "fax_cross_entropy": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "fax_timing_enable": (i32, [i32]),
+        "fax_timing_report": (i32, [P(FaxKernelTime), i32, P(i32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -241,6 +248,18 @@ def fax_attention_fwd(dtype, B, S, H, dh, qkv, ctx, lse, path=PATH_AUTO, stream=
 def fax_attention_bwd(dtype, B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, path=PATH_AUTO, stream=None):
     _check(_lib.fax_attention_bwd(dtype, B, S, H, dh, _ptr(qkv), _ptr(ctx), _ptr(lse), _ptr(dctx), _ptr(dqkv),
                                   _ptr(delta), path, _stream(stream)))
+
+
+def fax_timing_enable(on):
+    _check(_lib.fax_timing_enable(int(on)))
+
+
+def fax_timing_report(capacity=64):
+    """-> list of dicts {name, launches, ms, work, unit} (unit 0 = flop, 1 = byte)."""
+    rows = (FaxKernelTime * capacity)()
+    n = C.c_int(0)
+    _check(_lib.fax_timing_report(rows, capacity, C.byref(n)))
+    return [dict(name=r.name.decode(), launches=r.launches, ms=r.ms, work=r.work, unit=r.unit) for r in rows[:n.value]]
 
 
 def fax_cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, stream=None):

@@ -2,8 +2,12 @@
 // Everything here runs on the host; validation precedes the first launch.
 #include <cstdarg>
 #include <cstdio>
+#include <atomic>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <string>
+#include <vector>
 
 #include "fax_internal.h"
 
@@ -21,6 +25,48 @@ void set_error(const char* fmt, ...) {
 int hip_fail(hipError_t e, const char* what) {
   set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
   return FAX_ERR_HIP;
+}
+
+// ---- per-kernel timing ------------------------------------------------------------------------
+struct TimingRecord {
+  std::string name;
+  int unit;
+  double work;
+  hipEvent_t start, stop;
+};
+static std::mutex g_timing_mu;
+static std::atomic<bool> g_timing_on{false};
+static std::vector<TimingRecord*> g_timing;
+
+bool timing_on() { return g_timing_on.load(std::memory_order_relaxed); }
+
+void timing_begin(const char* name, int unit, double work, hipStream_t s, void** token) {
+  TimingRecord* r = new TimingRecord{name, unit, work, nullptr, nullptr};
+  if (hipEventCreate(&r->start) != hipSuccess || hipEventCreate(&r->stop) != hipSuccess ||
+      hipEventRecord(r->start, s) != hipSuccess) {
+    if (r->start) (void)hipEventDestroy(r->start);
+    if (r->stop) (void)hipEventDestroy(r->stop);
+    delete r;
+    return;
+  }
+  *token = r;
+}
+
+void timing_end(void* token, hipStream_t s) {
+  TimingRecord* r = static_cast<TimingRecord*>(token);
+  (void)hipEventRecord(r->stop, s);
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_timing.push_back(r);
+}
+
+static void timing_clear() {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (TimingRecord* r : g_timing) {
+    (void)hipEventDestroy(r->start);
+    (void)hipEventDestroy(r->stop);
+    delete r;
+  }
+  g_timing.clear();
 }
 
 static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -158,7 +204,9 @@ static int attention_fwd(int dtype, int B, int S, int H, int dh, const void* qkv
     set_error("attention: dtype %d, S=%d, dh=%d is not covered by the MFMA kernel", dtype, S, dh);
     return FAX_ERR_UNSUPPORTED;
   }
-  if (ok && path != PATH_SIMT) return attn_fwd_mfma(B, S, H, dh, qkv, ctx, lse, s);
+  const bool mfma = ok && path != PATH_SIMT;
+  Timed t_(mfma ? "attention_fwd_mfma" : "attention_fwd_scalar", WORK_FLOP, 2.0 * B * H * (double)S * S * dh, s);
+  if (mfma) return attn_fwd_mfma(B, S, H, dh, qkv, ctx, lse, s);
   return attn_fwd_simt(dtype, B, S, H, dh, qkv, ctx, lse, s);
 }
 
@@ -169,7 +217,9 @@ static int attention_bwd(int dtype, int B, int S, int H, int dh, const void* qkv
     set_error("attention: dtype %d, S=%d, dh=%d is not covered by the MFMA kernel", dtype, S, dh);
     return FAX_ERR_UNSUPPORTED;
   }
-  if (ok && path != PATH_SIMT) return attn_bwd_mfma(B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s);
+  const bool mfma = ok && path != PATH_SIMT;
+  Timed t_(mfma ? "attention_bwd_mfma" : "attention_bwd_scalar", WORK_FLOP, 4.0 * B * H * (double)S * S * dh, s);
+  if (mfma) return attn_bwd_mfma(B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s);
   return attn_bwd_simt(dtype, B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s);
 }
 
@@ -425,7 +475,7 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
   if (lowp && misaligned(lowp)) { set_error("lowp is not 16-byte aligned"); return FAX_ERR_INVALID_ARG; }
   if (!hp) { set_error("hp is NULL"); return FAX_ERR_INVALID_ARG; }
   if (step < 1) { set_error("step must be >= 1, got %d", step); return FAX_ERR_INVALID_ARG; }
-  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f)) {
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
     set_error("betas must lie in [0, 1)");
     return FAX_ERR_INVALID_ARG;
   }
@@ -528,6 +578,39 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
     void* const* G = (void* const*)tensor_list(&grads->blocks[l]);
     for (int i = 0; i < 12; i++) FAX_TRY(upd(P[i], Ms[i], Mo[i], Vo[i], G[i], n[i]));
   }
+  return FAX_OK;
+}
+
+int fax_timing_enable(int on) {
+  if (on) timing_clear();
+  g_timing_on.store(on != 0);
+  return FAX_OK;
+}
+
+int fax_timing_report(FaxKernelTime* out, int capacity, int* count) {
+  if (!out || !count || capacity <= 0) { set_error("fax_timing_report: bad arguments"); return FAX_ERR_INVALID_ARG; }
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  std::map<std::string, FaxKernelTime> rows;
+  for (TimingRecord* r : g_timing) {
+    FAX_HIP(hipEventSynchronize(r->stop));
+    float ms = 0.f;
+    FAX_HIP(hipEventElapsedTime(&ms, r->start, r->stop));
+    FaxKernelTime& k = rows[r->name];
+    if (k.launches == 0) {
+      memset(&k, 0, sizeof(k));
+      snprintf(k.name, sizeof(k.name), "%s", r->name.c_str());
+      k.unit = r->unit;
+    }
+    k.launches += 1;
+    k.ms += ms;
+    k.work += r->work;
+  }
+  int n = 0;
+  for (auto& kv : rows) {
+    if (n == capacity) break;
+    out[n++] = kv.second;
+  }
+  *count = n;
   return FAX_OK;
 }
 

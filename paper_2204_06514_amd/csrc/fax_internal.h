@@ -74,6 +74,8 @@ int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool 
 int attn_fwd_simt(int dtype, int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, hipStream_t s);
 int attn_bwd_simt(int dtype, int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
                   const void* dctx, void* dqkv, float* delta, hipStream_t s);
+// delta[b,h,i] = sum_d dctx[b,i,h,d] ctx[b,i,h,d]
+int attn_delta(int dtype, int B, int S, int H, int dh, const void* ctx, const void* dctx, float* delta, hipStream_t s);
 bool attn_mfma_supported(int dtype, int B, int S, int H, int dh);
 int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, hipStream_t s);
 int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
@@ -90,6 +92,22 @@ int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void*
 int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
           hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// ---- optional per-kernel timing (see fax_timing_enable) ------------------------------------
+enum { WORK_FLOP = 0, WORK_BYTE = 1 };
+bool timing_on();
+void timing_begin(const char* name, int unit, double work, hipStream_t s, void** token);
+void timing_end(void* token, hipStream_t s);
+struct Timed {
+  void* token = nullptr;
+  hipStream_t s;
+  Timed(const char* name, int unit, double work, hipStream_t stream) : s(stream) {
+    if (timing_on()) timing_begin(name, unit, work, s, &token);
+  }
+  ~Timed() {
+    if (token) timing_end(token, s);
+  }
+};
 
 // ---- device helpers -----------------------------------------------------------------------------
 #ifdef __HIPCC__

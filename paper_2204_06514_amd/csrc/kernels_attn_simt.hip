@@ -186,6 +186,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simt_kernel(int S, int H, in
   }
 }
 
+int attn_delta(int dtype, int B, int S, int H, int dh, const void* ctx, const void* dctx, float* delta, hipStream_t s) {
+  dim3 grid((S + 3) / 4, B * H);
+  if (dtype == FAX_F32)
+    hipLaunchKernelGGL((attn_delta_kernel<float>), grid, dim3(256), 0, s, S, H, dh, (const float*)ctx, (const float*)dctx,
+                       delta);
+  else
+    hipLaunchKernelGGL((attn_delta_kernel<bf16_t>), grid, dim3(256), 0, s, S, H, dh, (const bf16_t*)ctx,
+                       (const bf16_t*)dctx, delta);
+  FAX_LAUNCH_CHECK("attn_delta");
+  return FAX_OK;
+}
+
 template <typename T>
 static int attn_fwd_simt_t(int B, int S, int H, int dh, const T* qkv, T* ctx, float* lse, hipStream_t s) {
   dim3 grid((S + 3) / 4, B * H);

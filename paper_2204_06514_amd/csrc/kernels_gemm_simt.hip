@@ -1,6 +1,8 @@
 // Scalar-FMA GEMM: true fp32 multiply-add for the fp32 workloads, and the fallback for bf16
 // shapes that the MFMA kernel's tiles do not divide.  Any M, N, K, any operand orientation.
 // 64x64x16 tile, 256 threads, 4x4 outputs per thread, operands staged through LDS as fp32.
+#include <cstdio>
+
 #include "fax_internal.h"
 
 namespace fax {
@@ -88,7 +90,21 @@ int gemm_simt(const GemmArgs& g, hipStream_t s) {
   return gemm_simt_t<bf16_t>(g, s);
 }
 
+static int gemm_dispatch(const GemmArgs& g, hipStream_t s);
+
 int gemm(const GemmArgs& g, hipStream_t s) {
+  if (!timing_on()) return gemm_dispatch(g, s);
+  // name the variant the way the kernel templates are instantiated: operand orientation
+  // (k = contraction index contiguous, m = row/column index contiguous) and epilogue
+  const bool mfma = g.path != PATH_SIMT && gemm_mfma_supported(g);
+  char name[64];
+  snprintf(name, sizeof(name), "gemm_%s_A%c_B%c_%s", mfma ? "mfma" : "scalar", g.ta ? 'm' : 'k', g.tb ? 'k' : 'm',
+           g.c_f32 ? "f32out" : g.epi == EPI_GELU ? "gelu" : g.epi == EPI_DGELU ? "dgelu" : "store");
+  Timed t(name, WORK_FLOP, 2.0 * g.M * g.N * g.K, s);
+  return gemm_dispatch(g, s);
+}
+
+static int gemm_dispatch(const GemmArgs& g, hipStream_t s) {
   if (g.path == PATH_SIMT) return gemm_simt(g, s);
   if (g.path == PATH_MFMA) {
     if (!gemm_mfma_supported(g)) {

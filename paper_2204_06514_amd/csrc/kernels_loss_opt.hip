@@ -118,6 +118,7 @@ static int ce_t(int N, int V, const T* logits, const int32_t* labels, T* dlogits
 int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits, float* row_loss,
                   float* loss_out, hipStream_t s) {
   if (N == 0) return FAX_OK;
+  Timed t_("cross_entropy", WORK_BYTE, 2.0 * N * V * (dtype == FAX_F32 ? 4.0 : 2.0), s);
   if (dtype == FAX_F32) return ce_t<float>(N, V, (const float*)logits, labels, (float*)dlogits, row_loss, loss_out, s);
   return ce_t<bf16_t>(N, V, (const bf16_t*)logits, labels, (bf16_t*)dlogits, row_loss, loss_out, s);
 }
@@ -160,6 +161,7 @@ __global__ __launch_bounds__(256) void embed_bwd_pos_kernel(int B, int S, int D,
 int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb, void* x0,
               hipStream_t s) {
   if (B * S == 0) return FAX_OK;
+  Timed t_("embed_fwd", WORK_BYTE, 3.0 * B * S * D * (dtype == FAX_F32 ? 4.0 : 2.0), s);
   if (dtype == FAX_F32)
     hipLaunchKernelGGL((embed_fwd_kernel<float>), dim3(B * S), dim3(256), 0, s, S, D, tokens, (const float*)tok_emb,
                        (const float*)pos_emb, (float*)x0);
@@ -173,6 +175,7 @@ int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void*
 int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
               hipStream_t s) {
   if (B * S == 0) return FAX_OK;
+  Timed t_("embed_bwd", WORK_BYTE, 2.0 * B * S * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * B * S * D + 4.0 * S * D, s);
   if (dtype == FAX_F32) {
     hipLaunchKernelGGL((embed_bwd_tok_kernel<float>), dim3(B * S), dim3(256), 0, s, D, tokens, (const float*)dx0, g_tok);
     hipLaunchKernelGGL((embed_bwd_pos_kernel<float>), dim3(S), dim3(256), 0, s, B, S, D, (const float*)dx0, g_pos);
@@ -233,13 +236,14 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict_
 int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
           hipStream_t s) {
   if (n == 0) return FAX_OK;
+  Timed t_("adamw", WORK_BYTE, (lowp ? 30.0 : 28.0) * (double)n, s);
   AdamScalars a;
-  a.b1 = hp.beta1; a.b2 = hp.beta2;
-  a.one_m_b1 = 1.f - hp.beta1; a.one_m_b2 = 1.f - hp.beta2;
-  a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)hp.beta1, (double)step)));
-  a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)hp.beta2, (double)step)));
-  a.lr = hp.lr; a.eps = hp.eps;
-  a.decay = 1.f - hp.lr * hp.wd;
+  a.b1 = (float)hp.beta1; a.b2 = (float)hp.beta2;
+  a.one_m_b1 = (float)(1.0 - hp.beta1); a.one_m_b2 = (float)(1.0 - hp.beta2);
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow(hp.beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp.beta2, (double)step)));
+  a.lr = (float)hp.lr; a.eps = (float)hp.eps;
+  a.decay = (float)(1.0 - hp.lr * hp.wd);
   size_t blocks = (n / 4 + 255) / 256;
   if (blocks < 1) blocks = 1;
   if (blocks > 256 * 16) blocks = 256 * 16;

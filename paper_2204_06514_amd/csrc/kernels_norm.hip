@@ -144,6 +144,7 @@ static int ln_fwd_t(int rows, int D, const T* x, const T* gamma, const T* beta, 
 int ln_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const void* beta, float eps, void* h,
            float* mu, float* rstd, hipStream_t s) {
   if (rows == 0) return FAX_OK;
+  Timed t_("layernorm_fwd", WORK_BYTE, 2.0 * rows * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * rows, s);
   if (dtype == FAX_F32)
     return ln_fwd_t<float>(rows, D, (const float*)x, (const float*)gamma, (const float*)beta, eps, (float*)h, mu, rstd, s);
   return ln_fwd_t<bf16_t>(rows, D, (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, eps, (bf16_t*)h, mu, rstd, s);
@@ -334,6 +335,7 @@ int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const floa
            const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta, bool accumulate, void* ws,
            hipStream_t s) {
   if (rows == 0) return FAX_OK;
+  Timed t_("layernorm_bwd", WORK_BYTE, (dres ? 4.0 : 3.0) * rows * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * rows, s);
   if (dtype == FAX_F32)
     return ln_bwd_t<float>(rows, D, (const float*)dh, (const float*)x, mu, rstd, (const float*)gamma, (const float*)dres,
                            (float*)dx, dgamma, dbeta, accumulate, (float*)ws, s);
@@ -389,6 +391,7 @@ size_t colsum_ws_bytes(int N) { return (size_t)CS_PARTS * (size_t)N * sizeof(flo
 
 int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws, hipStream_t s) {
   if (N == 0) return FAX_OK;
+  Timed t_("colsum", WORK_BYTE, 1.0 * rows * N * (dtype == FAX_F32 ? 4.0 : 2.0), s);
   const int parts = max(1, min(CS_PARTS, (rows + 3) / 4));
   float* partial = (float*)ws;
   if (dtype == FAX_F32) {

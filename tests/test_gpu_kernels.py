@@ -126,6 +126,22 @@ def test_attention_scalar_path(dtype, B, S, H, dh):
     assert e_ctx <= t and e_lse <= (2e-5 if dtype == "f32" else 1e-4) and max(errs) <= t, (e_ctx, e_lse, errs)
 
 
+@pytest.mark.parametrize("B,S,H,dh,scale", [(2, 128, 2, 64, 1.0), (1, 384, 3, 128, 1.0), (2, 512, 2, 64, 2.0),
+                                            (1, 1024, 2, 128, 0.5)])
+def test_attention_mfma_path(B, S, H, dh, scale):
+    """scale widens the score distribution (std = scale^2 sqrt(dh)): peaky softmax rows at 2.0."""
+    e_ctx, e_lse, errs = _attention_case("bf16", B, S, H, dh, fax.PATH_MFMA, scale)
+    assert e_ctx <= 8e-3 and e_lse <= 2e-4 and max(errs) <= 1e-2, (e_ctx, e_lse, errs)
+
+
+def test_attention_mfma_rejects_uncovered_shapes():
+    q = torch.zeros((1, 100, 3 * 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_attention_fwd(fax.FAX_BF16, 1, 100, 1, 64, q, torch.empty((1, 100, 64), dtype=torch.bfloat16, device=DEV),
+                              torch.empty((1, 1, 100), device=DEV), fax.PATH_MFMA)
+    assert e.value.status == fax.FAX_ERR_UNSUPPORTED
+
+
 # --------------------------------------------------------------------- cross-entropy
 @pytest.mark.parametrize("dtype,N,V", [("f32", 64, 1000), ("f32", 7, 37), ("bf16", 50, 51200), ("bf16", 33, 777),
                                        ("bf16", 3, 70000)])

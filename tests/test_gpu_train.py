@@ -1,0 +1,112 @@
+"""Parity of fax_train_step (embedding, blocks, final LayerNorm, tied output projection, mean
+cross-entropy, all gradients, AdamW) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2204_06514_amd as fax
+from oracle import transformer as orc
+from workloads import BlockShape, ModelShape, make_model_inputs, PARAM_NAMES
+from workloads.configs import ADAMW_DEFAULT
+from helpers import DEV, TDTYPE, to_dev, to_np, err, tol, dims_of
+
+pytestmark = pytest.mark.gpu
+
+TOP = ("tok_emb", "pos_emb", "lnf_g", "lnf_b")
+
+
+def _dev_params(p, dtype):
+    d = {k: to_dev(p[k], dtype) for k in TOP}
+    d["blocks"] = [{k: to_dev(bp[k], dtype) for k in PARAM_NAMES} for bp in p["blocks"]]
+    return d
+
+
+def _like(d, fill=None, dtype=torch.float32, src=None):
+    def mk(t, s):
+        if src is not None:
+            return s.to(dtype).clone()
+        return torch.full(t.shape, fill, dtype=dtype, device=DEV)
+    out = {k: mk(d[k], src[k] if src else None) for k in TOP}
+    out["blocks"] = [{k: mk(b[k], src["blocks"][i][k] if src else None) for k in PARAM_NAMES}
+                     for i, b in enumerate(d["blocks"])]
+    return out
+
+
+def run_train_step(ms, p, tok, lab, update, step=1):
+    sh = ms.blk
+    md = fax.FaxModelDims(dims_of(sh), sh.L, ms.V, ms.S_max, 0 if update else fax.FAX_FLAG_SKIP_UPDATE)
+    params = _dev_params(p, sh.dtype)
+    if sh.dtype == "f32":
+        master = params                       # one fp32 copy, updated in place
+    else:
+        master = _like(params, src=params)    # fp32 master copies of the bf16 parameters
+    m = _like(params, 0.0); v = _like(params, 0.0); grads = _like(params, 7.0)   # 7: must be overwritten
+    wsb = fax.fax_train_workspace_bytes(md)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    loss = torch.zeros(4, device=DEV)
+    hp = fax.FaxAdamW(**ADAMW_DEFAULT)
+    fax.fax_train_step(md, params, master, m, v, grads, torch.from_numpy(tok).to(DEV), torch.from_numpy(lab).to(DEV),
+                       hp, step, loss, ws, wsb)
+    torch.cuda.synchronize()
+    return loss[0].item(), params, master, m, v, grads
+
+
+def _walk(d):
+    for k in TOP:
+        yield k, (lambda t, k=k: t[k])
+    for l in range(len(d["blocks"])):
+        for k in PARAM_NAMES:
+            yield "blocks[%d].%s" % (l, k), (lambda t, l=l, k=k: t["blocks"][l][k])
+
+
+CASES = [
+    ModelShape(BlockShape(B=2, S=24, D=32, H=2, dh=16, F=64, dtype="f32", sigma_w=0.1, L=2), V=97, S_max=32),
+    ModelShape(BlockShape(B=2, S=128, D=128, H=2, dh=64, F=256, dtype="bf16", sigma_w=0.05, L=2), V=512, S_max=128),
+    ModelShape(BlockShape(B=1, S=40, D=72, H=3, dh=24, F=100, dtype="bf16", sigma_w=0.05, L=1), V=333, S_max=48),
+]
+
+
+@pytest.mark.parametrize("ms", CASES, ids=lambda m: "%s_D%d_V%d" % (m.blk.dtype, m.blk.D, m.V))
+def test_train_step_gradients_then_update(ms):
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=3, generic=True)
+    loss_ref, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    # gradients only
+    loss, params, _, _, _, grads = run_train_step(ms, p, tok, lab, update=False)
+    assert abs(loss - loss_ref) <= (1e-5 if sh.dtype == "f32" else 2e-3) * abs(loss_ref)
+    t = tol(sh.dtype)
+    bad = {}
+    for name, get in _walk(grads):
+        e = err(to_np(get(grads)), get(g_ref), sh.dtype)
+        if not e <= t:
+            bad[name] = e
+    assert not bad, bad
+    for name, get in _walk(params):   # parameters untouched
+        assert np.array_equal(to_np(get(params)), get(p)), name
+    # full step: compare updated parameters; the key third of bqkv is excluded, its gradient is
+    # analytically zero so the first Adam step turns rounding noise into a full-size +-lr move
+    loss, params, master, m, v, grads = run_train_step(ms, p, tok, lab, update=True)
+    hp = ADAMW_DEFAULT
+    Hd = sh.Hd
+    bad = {}
+    for name, get in _walk(master):
+        ref, _, _ = orc.adamw(get(p), 0.0, 0.0, get(g_ref), hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"], 1)
+        got = to_np(get(master))
+        if name.endswith("bqkv"):
+            ref = np.concatenate([ref[:Hd], ref[2 * Hd:]]); got = np.concatenate([got[:Hd], got[2 * Hd:]])
+        # a first Adam step moves every element by about lr; parameters are O(sigma) or O(1), so the
+        # updated values must agree far tighter than the gradient bar
+        e = np.abs(got - ref).max()
+        if not e <= 2.5 * hp["lr"] * (1e-3 if sh.dtype == "f32" else 1.0):
+            bad[name] = e
+        if sh.dtype == "bf16":
+            assert torch.equal(get(params), get(master).to(torch.bfloat16)), name
+    assert not bad, bad
+
+
+def test_train_step_pos_rows_beyond_sequence_get_zero_gradient():
+    ms = CASES[2]
+    p, tok, lab = make_model_inputs(ms, seed=5)
+    _, _, _, _, _, grads = run_train_step(ms, p, tok, lab, update=False)
+    assert torch.all(grads["pos_emb"][ms.blk.S:] == 0)
+    assert torch.any(grads["pos_emb"][:ms.blk.S] != 0)
