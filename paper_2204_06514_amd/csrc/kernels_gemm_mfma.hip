@@ -89,7 +89,19 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
 }
 
 // Epilogue flavours, fixed at compile time so the 16 x TM x TN stores unroll into straight code.
-enum { EM_STORE = 0, EM_GELU = 1, EM_DGELU = 2, EM_F32 = 3 };
+enum { EM_STORE = 0, EM_GELU_TANH = 1, EM_DGELU_TANH = 2, EM_F32 = 3, EM_GELU_ERF = 4, EM_DGELU_ERF = 5 };
+
+// tanh-form GELU through the logistic function: (1 + tanh z) / 2 = 1 / (1 + exp(-2 z)), one
+// v_exp_f32 and one v_rcp_f32 per element, a few ulp in fp32 (the outputs are rounded to bf16).
+__device__ __forceinline__ float sigmoid2z(float u) {
+  const float z2 = 1.5957691216057308f * (u + 0.044715f * u * u * u);  // 2 sqrt(2/pi) (u + k u^3)
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z2));
+}
+__device__ __forceinline__ float gelu_tanh_fast(float u) { return u * sigmoid2z(u); }
+__device__ __forceinline__ float gelu_tanh_grad_fast(float u) {
+  const float sg = sigmoid2z(u);
+  return sg + u * sg * (1.f - sg) * 1.5957691216057308f * (1.f + 0.134145f * u * u);
+}
 
 template <int EM>
 __device__ __forceinline__ void mfma_epilogue(const EpiArgs& e, int m, int n, float acc) {
@@ -101,12 +113,16 @@ __device__ __forceinline__ void mfma_epilogue(const EpiArgs& e, int m, int n, fl
   if (EM == EM_STORE && e.C2) ((bf16_t*)e.C2)[(size_t)m * e.ldc2 + n] = (bf16_t)acc;
   if (e.bias) acc += (float)((const bf16_t*)e.bias)[n];
   if (e.R) acc += (float)((const bf16_t*)e.R)[(size_t)m * e.ldr + n];
-  if (EM == EM_GELU) {
+  if (EM == EM_GELU_TANH || EM == EM_GELU_ERF) {
     ((bf16_t*)e.C)[(size_t)m * e.ldc + n] = (bf16_t)acc;
-    ((bf16_t*)e.C2)[(size_t)m * e.ldc2 + n] = (bf16_t)gelu_f(acc, e.gelu_form);
+    const float a = EM == EM_GELU_TANH ? gelu_tanh_fast(acc) : gelu_f(acc, FAX_GELU_ERF);
+    ((bf16_t*)e.C2)[(size_t)m * e.ldc2 + n] = (bf16_t)a;
     return;
   }
-  if (EM == EM_DGELU) acc *= gelu_grad_f((float)((const bf16_t*)e.U)[(size_t)m * e.ldu + n], e.gelu_form);
+  if (EM == EM_DGELU_TANH || EM == EM_DGELU_ERF) {
+    const float u = (float)((const bf16_t*)e.U)[(size_t)m * e.ldu + n];
+    acc *= EM == EM_DGELU_TANH ? gelu_tanh_grad_fast(u) : gelu_grad_f(u, FAX_GELU_ERF);
+  }
   ((bf16_t*)e.C)[(size_t)m * e.ldc + n] = (bf16_t)acc;
 }
 
@@ -209,6 +225,10 @@ static int pick_tile(const GemmArgs& g) {
 bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.dtype != FAX_BF16) return false;
   if (g.c_f32 && (g.bias || g.R || g.C2 || g.epi != EPI_NONE)) return false;  // fp32 C is the plain weight-gradient form
+  // the GELU epilogues exist for the orientations the block uses them in: forward (A [M,K], B [K,N])
+  // and input-gradient (A [M,K], B [N,K])
+  if (g.epi == EPI_GELU && (g.ta || g.tb)) return false;
+  if (g.epi == EPI_DGELU && (g.ta || !g.tb)) return false;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % GK != 0) return false;
   if (g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return false;
   return pick_tile(g) != 0;
@@ -230,28 +250,31 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   return FAX_OK;
 }
 
-template <int BT, bool A_KC, bool B_KC>
-static int dispatch_epi(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
-  if (g.c_f32) return launch_mfma<BT, A_KC, B_KC, EM_F32>(g, e, s);
-  if (g.epi == EPI_GELU) return launch_mfma<BT, A_KC, B_KC, EM_GELU>(g, e, s);
-  if (g.epi == EPI_DGELU) return launch_mfma<BT, A_KC, B_KC, EM_DGELU>(g, e, s);
-  return launch_mfma<BT, A_KC, B_KC, EM_STORE>(g, e, s);
-}
-
 template <int BT>
-static int dispatch_layout(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
+static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   const bool a_kc = !g.ta, b_kc = g.tb;
-  if (a_kc && b_kc) return dispatch_epi<BT, true, true>(g, e, s);
-  if (a_kc && !b_kc) return dispatch_epi<BT, true, false>(g, e, s);
-  if (!a_kc && b_kc) return dispatch_epi<BT, false, true>(g, e, s);
-  return dispatch_epi<BT, false, false>(g, e, s);
+  const bool erf = g.gelu_form == FAX_GELU_ERF;
+  if (g.epi == EPI_GELU)
+    return erf ? launch_mfma<BT, true, false, EM_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EM_GELU_TANH>(g, e, s);
+  if (g.epi == EPI_DGELU)
+    return erf ? launch_mfma<BT, true, true, EM_DGELU_ERF>(g, e, s) : launch_mfma<BT, true, true, EM_DGELU_TANH>(g, e, s);
+  if (g.c_f32) {
+    if (a_kc && b_kc) return launch_mfma<BT, true, true, EM_F32>(g, e, s);
+    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EM_F32>(g, e, s);
+    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EM_F32>(g, e, s);
+    return launch_mfma<BT, false, false, EM_F32>(g, e, s);
+  }
+  if (a_kc && b_kc) return launch_mfma<BT, true, true, EM_STORE>(g, e, s);
+  if (a_kc && !b_kc) return launch_mfma<BT, true, false, EM_STORE>(g, e, s);
+  if (!a_kc && b_kc) return launch_mfma<BT, false, true, EM_STORE>(g, e, s);
+  return launch_mfma<BT, false, false, EM_STORE>(g, e, s);
 }
 
 int gemm_mfma(const GemmArgs& g, hipStream_t s) {
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
             g.accumulate ? 1 : 0};
-  if (pick_tile(g) == 256) return dispatch_layout<256>(g, e, s);
-  return dispatch_layout<128>(g, e, s);
+  if (pick_tile(g) == 256) return dispatch<256>(g, e, s);
+  return dispatch<128>(g, e, s);
 }
 
 }  // namespace fax

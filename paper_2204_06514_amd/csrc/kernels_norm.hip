@@ -1,16 +1,16 @@
 // LayerNorm forward/backward and column sums: HBM-bound kernels.
 //
 // Forward reads each row once (16-byte loads, row cached in registers), writes it once.
-// Backward reads dh and x once, writes dx once; the per-column sums for dgamma/dbeta are
-// kept in registers across a strip of rows, written as one partial row per block and
-// folded by a second small kernel, so the result does not depend on scheduling order.
+// Backward: a row kernel reads dh and x once and writes dx once; the per-column sums for
+// dgamma/dbeta come from a second, column-parallel pass over dh and x (strips of rows summed
+// in registers, then folded in a fixed order), so no result depends on scheduling order.
 #include "fax_internal.h"
 
 namespace fax {
 
 static constexpr int LN_MAXV = 8;      // 16-byte vectors cached per thread
 static constexpr int LN_THREADS = 256;
-static constexpr int RED_PARTS = 512;  // partial rows produced by strip kernels
+static constexpr int CS_PARTS = 128;   // row strips of the column-sum kernels
 
 // Sum `v` over the TPR consecutive threads that share a row.  TPR in {64,128,256}.
 template <int TPR>
@@ -151,145 +151,189 @@ int ln_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const v
 }
 
 // ---------------------------------------------------------------------------------------------
-// Backward.  Block b handles rows b*RPB + k*gridDim.x*RPB ...; each thread owns the same
-// columns in every row, so dgamma/dbeta partials stay in registers.
-// partial layout: [gridDim.x * RPB][2][D] fp32 (dgamma then dbeta).
+// Backward, row part: dx = rstd (g - mean(g) - xhat mean(g xhat)) [+ dres], g = dh * gamma.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int TPR>
-__global__ __launch_bounds__(LN_THREADS) void ln_bwd_kernel(int rows, int D, const T* __restrict__ dh,
-                                                            const T* __restrict__ x, const float* __restrict__ mu,
-                                                            const float* __restrict__ rstd,
-                                                            const T* __restrict__ gamma, const T* __restrict__ dres,
-                                                            T* __restrict__ dx, float* __restrict__ partial) {
+__global__ __launch_bounds__(LN_THREADS) void ln_bwd_dx_kernel(int rows, int D, const T* __restrict__ dh,
+                                                               const T* __restrict__ x, const float* __restrict__ mu,
+                                                               const float* __restrict__ rstd,
+                                                               const T* __restrict__ gamma, const T* __restrict__ dres,
+                                                               T* __restrict__ dx) {
   using V = Vec16<T>;
   __shared__ float red[LN_THREADS / 64];
   constexpr int RPB = LN_THREADS / TPR;
   const int tr = threadIdx.x % TPR;
-  const int sub = threadIdx.x / TPR;
+  const int row = blockIdx.x * RPB + threadIdx.x / TPR;
+  const bool live = row < rows;
   const int nvec = D / V::N;
-  float ag[LN_MAXV][V::N], ab[LN_MAXV][V::N];
-  V gv[LN_MAXV];
+  const size_t off = (size_t)(live ? row : 0) * D;
+  const float m = live ? mu[row] : 0.f, r = live ? rstd[row] : 0.f;
+  V dv[LN_MAXV], xv[LN_MAXV];
+  float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < LN_MAXV; i++) {
-    int c = tr + i * TPR;
-    if (c < nvec) gv[i].load(gamma + c * V::N);
-#pragma unroll
-    for (int e = 0; e < V::N; e++) ag[i][e] = ab[i][e] = 0.f;
-  }
-  const int iters = (rows + gridDim.x * RPB - 1) / (gridDim.x * RPB);
-  for (int it = 0; it < iters; it++) {
-    const int row = (it * gridDim.x + blockIdx.x) * RPB + sub;
-    const bool live = row < rows;
-    const size_t off = (size_t)(live ? row : 0) * D;
-    const float m = live ? mu[row] : 0.f, r = live ? rstd[row] : 0.f;
-    V dv[LN_MAXV], xv[LN_MAXV];
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < LN_MAXV; i++) {
-      int c = tr + i * TPR;
-      if (c < nvec) {
-        dv[i].load(dh + off + c * V::N);
-        xv[i].load(x + off + c * V::N);
-#pragma unroll
-        for (int e = 0; e < V::N; e++) {
-          float xh = (xv[i].get(e) - m) * r;
-          float g = dv[i].get(e) * gv[i].get(e);
-          s1 += g;
-          s2 += g * xh;
-          if (live) {
-            ag[i][e] += dv[i].get(e) * xh;
-            ab[i][e] += dv[i].get(e);
-          }
-        }
-      }
-    }
-    const float m1 = row_sum<TPR>(s1, red) / D;
-    const float m2 = row_sum<TPR>(s2, red) / D;
-    if (live) {
-#pragma unroll
-      for (int i = 0; i < LN_MAXV; i++) {
-        int c = tr + i * TPR;
-        if (c < nvec) {
-          V o, rv;
-          if (dres) rv.load(dres + off + c * V::N);
-#pragma unroll
-          for (int e = 0; e < V::N; e++) {
-            float xh = (xv[i].get(e) - m) * r;
-            float g = dv[i].get(e) * gv[i].get(e);
-            float d = r * (g - m1 - xh * m2);
-            if (dres) d += rv.get(e);
-            o.set(e, d);
-          }
-          o.store(dx + off + c * V::N);
-        }
-      }
-    }
-  }
-  float* pg = partial + (size_t)(blockIdx.x * RPB + sub) * 2 * D;
-#pragma unroll
-  for (int i = 0; i < LN_MAXV; i++) {
-    int c = tr + i * TPR;
+    const int c = tr + i * TPR;
     if (c < nvec) {
+      V gv;
+      gv.load(gamma + c * V::N);
+      dv[i].load(dh + off + c * V::N);
+      xv[i].load(x + off + c * V::N);
 #pragma unroll
       for (int e = 0; e < V::N; e++) {
-        pg[c * V::N + e] = ag[i][e];
-        pg[D + c * V::N + e] = ab[i][e];
+        const float xh = (xv[i].get(e) - m) * r;
+        const float g = dv[i].get(e) * gv.get(e);
+        s1 += g;
+        s2 += g * xh;
       }
     }
   }
-}
-
-// Any D: one wave per row for dx; dgamma/dbeta partials through global atomics-free strips:
-// each wave owns a strip of rows and loops over columns, writing its own partial row.
-template <typename T>
-__global__ __launch_bounds__(LN_THREADS) void ln_bwd_generic_kernel(int rows, int D, const T* __restrict__ dh,
-                                                                    const T* __restrict__ x,
-                                                                    const float* __restrict__ mu,
-                                                                    const float* __restrict__ rstd,
-                                                                    const T* __restrict__ gamma,
-                                                                    const T* __restrict__ dres, T* __restrict__ dx,
-                                                                    float* __restrict__ partial) {
-  const int lane = threadIdx.x & 63;
-  const int wid = blockIdx.x * (LN_THREADS / 64) + (threadIdx.x >> 6);
-  const int nw = gridDim.x * (LN_THREADS / 64);
-  float* pg = partial + (size_t)wid * 2 * D;
-  for (int c = lane; c < D; c += 64) pg[c] = pg[D + c] = 0.f;
-  for (int row = wid; row < rows; row += nw) {
-    const size_t off = (size_t)row * D;
-    const float m = mu[row], r = rstd[row];
-    float s1 = 0.f, s2 = 0.f;
-    for (int c = lane; c < D; c += 64) {
-      float d = to_f(dh[off + c]);
-      float xh = (to_f(x[off + c]) - m) * r;
-      float g = d * to_f(gamma[c]);
-      s1 += g;
-      s2 += g * xh;
-      pg[c] += d * xh;
-      pg[D + c] += d;
-    }
-    const float m1 = wave_sum(s1) / D, m2 = wave_sum(s2) / D;
-    for (int c = lane; c < D; c += 64) {
-      float xh = (to_f(x[off + c]) - m) * r;
-      float g = to_f(dh[off + c]) * to_f(gamma[c]);
-      float d = r * (g - m1 - xh * m2);
-      if (dres) d += to_f(dres[off + c]);
-      dx[off + c] = from_f<T>(d);
+  const float m1 = row_sum<TPR>(s1, red) / D;
+  const float m2 = row_sum<TPR>(s2, red) / D;
+  if (!live) return;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; i++) {
+    const int c = tr + i * TPR;
+    if (c < nvec) {
+      V gv, o, rv;
+      gv.load(gamma + c * V::N);
+      if (dres) rv.load(dres + off + c * V::N);
+#pragma unroll
+      for (int e = 0; e < V::N; e++) {
+        const float xh = (xv[i].get(e) - m) * r;
+        const float g = dv[i].get(e) * gv.get(e);
+        float d = r * (g - m1 - xh * m2);
+        if (dres) d += rv.get(e);
+        o.set(e, d);
+      }
+      o.store(dx + off + c * V::N);
     }
   }
 }
 
-// out[n] (+)= sum_p partial[p*stride + n]
-__global__ __launch_bounds__(256) void fold_partials_kernel(int parts, size_t stride, int N,
-                                                            const float* __restrict__ partial,
-                                                            float* __restrict__ out, int accumulate) {
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
-  float s = 0.f;
-  for (int p = 0; p < parts; p++) s += partial[(size_t)p * stride + n];
-  out[n] = accumulate ? out[n] + s : s;
+template <typename T>
+__global__ __launch_bounds__(LN_THREADS) void ln_bwd_dx_generic_kernel(int rows, int D, const T* __restrict__ dh,
+                                                                       const T* __restrict__ x,
+                                                                       const float* __restrict__ mu,
+                                                                       const float* __restrict__ rstd,
+                                                                       const T* __restrict__ gamma,
+                                                                       const T* __restrict__ dres, T* __restrict__ dx) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * (LN_THREADS / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const size_t off = (size_t)row * D;
+  const float m = mu[row], r = rstd[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane; c < D; c += 64) {
+    const float xh = (to_f(x[off + c]) - m) * r;
+    const float g = to_f(dh[off + c]) * to_f(gamma[c]);
+    s1 += g;
+    s2 += g * xh;
+  }
+  const float m1 = wave_sum(s1) / D, m2 = wave_sum(s2) / D;
+  for (int c = lane; c < D; c += 64) {
+    const float xh = (to_f(x[off + c]) - m) * r;
+    const float g = to_f(dh[off + c]) * to_f(gamma[c]);
+    float d = r * (g - m1 - xh * m2);
+    if (dres) d += to_f(dres[off + c]);
+    dx[off + c] = from_f<T>(d);
+  }
 }
 
-size_t ln_bwd_ws_bytes(int D) { return (size_t)RED_PARTS * 4 * 2 * (size_t)D * sizeof(float); }
+// ---------------------------------------------------------------------------------------------
+// Column sums.  Block (bx, by): 64*VN columns, row strip by; its four waves take every fourth
+// row of the strip, sum in registers, combine through LDS and write one partial row.
+// MODE 0: out = sum_r a[r, n]                      (bias gradients)
+// MODE 1: out0 = sum_r a[r, n] xhat[r, n], out1 = sum_r a[r, n]   (dgamma, dbeta; a = dh)
+// partial layout: [MODE + 1][gridDim.y][N]
+// ---------------------------------------------------------------------------------------------
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void colsum_kernel(int rows, int N, const T* __restrict__ a, int lda,
+                                                     const T* __restrict__ x, const float* __restrict__ mu,
+                                                     const float* __restrict__ rstd, float* __restrict__ partial) {
+  using V = Vec16<T>;
+  __shared__ float red[4][(MODE + 1) * 64 * V::N];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 64 + lane) * V::N;
+  float acc[MODE + 1][V::N];
+#pragma unroll
+  for (int k = 0; k <= MODE; k++)
+#pragma unroll
+    for (int e = 0; e < V::N; e++) acc[k][e] = 0.f;
+  const bool vec_ok = (c0 + V::N <= N) && (lda % V::N == 0);
+  for (int r = blockIdx.y * 4 + wave; r < rows; r += gridDim.y * 4) {
+    const T* p = a + (size_t)r * lda + c0;
+    float m = 0.f, rs = 0.f;
+    if (MODE == 1) {
+      m = mu[r];
+      rs = rstd[r];
+    }
+    if (vec_ok) {
+      V v, xv;
+      v.load(p);
+      if (MODE == 1) xv.load(x + (size_t)r * lda + c0);
+#pragma unroll
+      for (int e = 0; e < V::N; e++) {
+        if (MODE == 1) {
+          acc[0][e] += v.get(e) * ((xv.get(e) - m) * rs);
+          acc[MODE][e] += v.get(e);
+        } else {
+          acc[0][e] += v.get(e);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < V::N; e++)
+        if (c0 + e < N) {
+          const float d = to_f(p[e]);
+          if (MODE == 1) {
+            acc[0][e] += d * ((to_f(x[(size_t)r * lda + c0 + e]) - m) * rs);
+            acc[MODE][e] += d;
+          } else {
+            acc[0][e] += d;
+          }
+        }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k <= MODE; k++)
+#pragma unroll
+    for (int e = 0; e < V::N; e++) red[wave][(k * 64 + lane) * V::N + e] = acc[k][e];
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int k = 0; k <= MODE; k++)
+#pragma unroll
+      for (int e = 0; e < V::N; e++) {
+        const int c = c0 + e;
+        if (c < N) {
+          const int i = (k * 64 + lane) * V::N + e;
+          partial[((size_t)k * gridDim.y + blockIdx.y) * N + c] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
+        }
+      }
+  }
+}
+
+// out[n] (+)= sum_p partial[p * N + n], p < parts: 64 columns per block, 4 waves split the parts.
+__global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, const float* __restrict__ partial,
+                                                            float* __restrict__ out, int accumulate) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  float s = 0.f;
+  if (n < N)
+    for (int p = wave; p < parts; p += 4) s += partial[(size_t)p * N + n];
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && n < N) {
+    s = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
+    out[n] = accumulate ? out[n] + s : s;
+  }
+}
+
+static int strips(int rows) { return max(1, min(CS_PARTS, (rows + 3) / 4)); }
+
+size_t ln_bwd_ws_bytes(int D) { return (size_t)2 * CS_PARTS * (size_t)D * sizeof(float); }
+size_t colsum_ws_bytes(int N) { return (size_t)CS_PARTS * (size_t)N * sizeof(float); }
 
 template <typename T>
 static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, const float* rstd, const T* gamma,
@@ -297,35 +341,28 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
                     hipStream_t s) {
   constexpr int VN = Vec16<T>::N;
   const int nvec = D / VN;
-  int parts;
   if (D % VN == 0 && nvec <= 256 * LN_MAXV) {
-    if (nvec <= 64 * LN_MAXV / 2) {
-      int grid = min(RED_PARTS, (rows + 3) / 4);
-      parts = grid * 4;
-      hipLaunchKernelGGL((ln_bwd_kernel<T, 64>), dim3(grid), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma, dres,
-                         dx, partial);
-    } else if (nvec <= 128 * LN_MAXV / 2) {
-      int grid = min(RED_PARTS, (rows + 1) / 2);
-      parts = grid * 2;
-      hipLaunchKernelGGL((ln_bwd_kernel<T, 128>), dim3(grid), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma,
-                         dres, dx, partial);
-    } else {
-      int grid = min(RED_PARTS, rows);
-      parts = grid;
-      hipLaunchKernelGGL((ln_bwd_kernel<T, 256>), dim3(grid), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma,
-                         dres, dx, partial);
-    }
+    if (nvec <= 64 * LN_MAXV / 2)
+      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 64>), dim3((rows + 3) / 4), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd,
+                         gamma, dres, dx);
+    else if (nvec <= 128 * LN_MAXV / 2)
+      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 128>), dim3((rows + 1) / 2), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd,
+                         gamma, dres, dx);
+    else
+      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 256>), dim3(rows), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma,
+                         dres, dx);
   } else {
-    int grid = min(RED_PARTS, (rows + 3) / 4);
-    parts = grid * 4;
-    hipLaunchKernelGGL((ln_bwd_generic_kernel<T>), dim3(grid), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma,
-                       dres, dx, partial);
+    hipLaunchKernelGGL((ln_bwd_dx_generic_kernel<T>), dim3((rows + 3) / 4), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu,
+                       rstd, gamma, dres, dx);
   }
-  FAX_LAUNCH_CHECK("ln_bwd");
-  const int gb = (D + 255) / 256;
-  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, (size_t)2 * D, D, partial, dgamma,
-                     accumulate ? 1 : 0);
-  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, (size_t)2 * D, D, partial + D, dbeta,
+  FAX_LAUNCH_CHECK("ln_bwd_dx");
+  const int parts = strips(rows);
+  hipLaunchKernelGGL((colsum_kernel<T, 1>), dim3((D + 64 * VN - 1) / (64 * VN), parts), dim3(256), 0, s, rows, D, dh, D, x,
+                     mu, rstd, partial);
+  FAX_LAUNCH_CHECK("ln_bwd_dgamma_dbeta");
+  const int gb = (D + 63) / 64;
+  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, D, partial, dgamma, accumulate ? 1 : 0);
+  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, D, partial + (size_t)parts * D, dbeta,
                      accumulate ? 1 : 0);
   FAX_LAUNCH_CHECK("ln_bwd_fold");
   return FAX_OK;
@@ -343,67 +380,22 @@ int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const floa
                           (const bf16_t*)dres, (bf16_t*)dx, dgamma, dbeta, accumulate, (float*)ws, s);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Column sums (bias gradients): block (bx, by) sums a strip of rows for 64*VN columns.
-// ---------------------------------------------------------------------------------------------
-static constexpr int CS_PARTS = 128;
-
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(int rows, int N, const T* __restrict__ a, int lda,
-                                                     float* __restrict__ partial) {
-  using V = Vec16<T>;
-  __shared__ float red[4][64 * V::N];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c0 = (blockIdx.x * 64 + lane) * V::N;
-  float acc[V::N];
-#pragma unroll
-  for (int e = 0; e < V::N; e++) acc[e] = 0.f;
-  const bool vec_ok = (c0 + V::N <= N) && (lda % V::N == 0);
-  for (int r = blockIdx.y * 4 + wave; r < rows; r += gridDim.y * 4) {
-    const T* p = a + (size_t)r * lda + c0;
-    if (vec_ok) {
-      V v;
-      v.load(p);
-#pragma unroll
-      for (int e = 0; e < V::N; e++) acc[e] += v.get(e);
-    } else {
-#pragma unroll
-      for (int e = 0; e < V::N; e++)
-        if (c0 + e < N) acc[e] += to_f(p[e]);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < V::N; e++) red[wave][lane * V::N + e] = acc[e];
-  __syncthreads();
-  if (wave == 0) {
-#pragma unroll
-    for (int e = 0; e < V::N; e++) {
-      int c = c0 + e;
-      if (c < N) {
-        int i = lane * V::N + e;
-        partial[(size_t)blockIdx.y * N + c] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
-      }
-    }
-  }
-}
-
-size_t colsum_ws_bytes(int N) { return (size_t)CS_PARTS * (size_t)N * sizeof(float); }
-
 int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws, hipStream_t s) {
   if (N == 0) return FAX_OK;
   Timed t_("colsum", WORK_BYTE, 1.0 * rows * N * (dtype == FAX_F32 ? 4.0 : 2.0), s);
-  const int parts = max(1, min(CS_PARTS, (rows + 3) / 4));
+  const int parts = strips(rows);
   float* partial = (float*)ws;
   if (dtype == FAX_F32) {
     dim3 grid((N + 64 * 4 - 1) / (64 * 4), parts);
-    hipLaunchKernelGGL((colsum_kernel<float>), grid, dim3(256), 0, s, rows, N, (const float*)a, lda, partial);
+    hipLaunchKernelGGL((colsum_kernel<float, 0>), grid, dim3(256), 0, s, rows, N, (const float*)a, lda, (const float*)nullptr,
+                       (const float*)nullptr, (const float*)nullptr, partial);
   } else {
     dim3 grid((N + 64 * 8 - 1) / (64 * 8), parts);
-    hipLaunchKernelGGL((colsum_kernel<bf16_t>), grid, dim3(256), 0, s, rows, N, (const bf16_t*)a, lda, partial);
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, 0>), grid, dim3(256), 0, s, rows, N, (const bf16_t*)a, lda,
+                       (const bf16_t*)nullptr, (const float*)nullptr, (const float*)nullptr, partial);
   }
   FAX_LAUNCH_CHECK("colsum");
-  hipLaunchKernelGGL(fold_partials_kernel, dim3((N + 255) / 256), dim3(256), 0, s, parts, (size_t)N, N, partial, out,
-                     accumulate ? 1 : 0);
+  hipLaunchKernelGGL(fold_partials_kernel, dim3((N + 63) / 64), dim3(256), 0, s, parts, N, partial, out, accumulate ? 1 : 0);
   FAX_LAUNCH_CHECK("colsum_fold");
   return FAX_OK;
 }
