@@ -14,6 +14,8 @@
 //
 // MFMA 32x32x16 lane layout (lane l): A/B operand = row/column (l & 31), k = 8 (l >> 5) + 0..7;
 // accumulator v = 0..15 holds C[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
+#include <type_traits>
+
 #include "fax_internal.h"
 
 namespace fax {
@@ -22,6 +24,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;  // 16 bytes in four consecutive VGPRs
 
 static constexpr int GK = 64;  // K slab
 
@@ -34,35 +37,83 @@ struct TileLds {
 
 // Global -> registers for one slab of one operand.
 template <int ROWS, bool KC>
-__device__ __forceinline__ void slab_load(uint4 (&r)[ROWS * GK / 8 / 256], const bf16_t* __restrict__ P, int ld,
+__device__ __forceinline__ void slab_load(u32x4 (&r)[ROWS * GK / 8 / 256], const bf16_t* __restrict__ P, int ld,
                                           int row0, int k0) {
 #pragma unroll
   for (int i = 0; i < TileLds<ROWS, KC>::NCHUNK; i++) {
     const int id = threadIdx.x + i * 256;
     if (KC) {
       const int row = id >> 3, c = id & 7;
-      r[i] = *reinterpret_cast<const uint4*>(P + (size_t)(row0 + row) * ld + k0 + c * 8);
+      r[i] = *reinterpret_cast<const u32x4*>(P + (size_t)(row0 + row) * ld + k0 + c * 8);
     } else {
       constexpr int CPR = ROWS / 8;
       const int kr = id / CPR, c = id % CPR;
-      r[i] = *reinterpret_cast<const uint4*>(P + (size_t)(k0 + kr) * ld + row0 + c * 8);
+      r[i] = *reinterpret_cast<const u32x4*>(P + (size_t)(k0 + kr) * ld + row0 + c * 8);
     }
   }
 }
 
+// Per-chunk versions of the two functions below, used by the pipelined main loop: chunk i of a
+// slab is the 16 bytes that thread t moves, id = t + 256 i.
+template <int ROWS, bool KC>
+__device__ __forceinline__ const bf16_t* chunk_src(const bf16_t* __restrict__ P, int ld, int row0, int k0, int i) {
+  const int id = threadIdx.x + i * 256;
+  if (KC) return P + (size_t)(row0 + (id >> 3)) * ld + k0 + (id & 7) * 8;
+  constexpr int CPR = ROWS / 8;
+  return P + (size_t)(k0 + id / CPR) * ld + row0 + (id % CPR) * 8;
+}
+template <int ROWS, bool KC>
+__device__ __forceinline__ int chunk_dst(int i) {
+  const int id = threadIdx.x + i * 256;
+  if (KC) return (id >> 3) * 128 + (((id & 7) ^ ((id >> 3) & 7)) << 4);
+  constexpr int CPR = ROWS / 8;
+  return (id / CPR) * TileLds<ROWS, KC>::STRIDE_MC + (id % CPR) * 16;
+}
+
+// Global loads issued through inline assembly.  The optimiser treats a plain load as free to
+// sink next to its first use, which here is an LDS store a whole loop iteration later, and that
+// exposes the global-memory latency once per slab.  A volatile asm statement keeps its place;
+// in exchange the wait is explicit: stage_wait<LO, HI, VM>() lets all but the VM most recent
+// loads finish (loads return in order) and takes registers LO..HI-1 as in/out operands, so
+// every later use of them depends on the wait.
+__device__ __forceinline__ void load_issue(u32x4& r, const bf16_t* src) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(r) : "v"(src) : "memory");
+}
+template <int LO, int HI, int VM, int NS>
+__device__ __forceinline__ void stage_wait(u32x4 (&r)[NS]) {
+  constexpr int C = HI - LO;
+  static_assert(C >= 1 && C <= 6 && HI <= NS, "chunk group size");
+  if constexpr (C == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r[LO]) : "n"(VM) : "memory");
+  if constexpr (C == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(r[LO]), "+v"(r[LO + 1]) : "n"(VM) : "memory");
+  if constexpr (C == 3)
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]) : "n"(VM) : "memory");
+  if constexpr (C == 4)
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]) : "n"(VM) : "memory");
+  if constexpr (C == 5)
+    asm volatile("s_waitcnt vmcnt(%5)"
+                 : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]), "+v"(r[LO + 4])
+                 : "n"(VM)
+                 : "memory");
+  if constexpr (C == 6)
+    asm volatile("s_waitcnt vmcnt(%6)"
+                 : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]), "+v"(r[LO + 4]), "+v"(r[LO + 5])
+                 : "n"(VM)
+                 : "memory");
+}
+
 // Registers -> LDS.
 template <int ROWS, bool KC>
-__device__ __forceinline__ void slab_store(const uint4 (&r)[ROWS * GK / 8 / 256], char* lds) {
+__device__ __forceinline__ void slab_store(const u32x4 (&r)[ROWS * GK / 8 / 256], char* lds) {
 #pragma unroll
   for (int i = 0; i < TileLds<ROWS, KC>::NCHUNK; i++) {
     const int id = threadIdx.x + i * 256;
     if (KC) {
       const int row = id >> 3, c = id & 7;
-      *reinterpret_cast<uint4*>(lds + row * 128 + ((c ^ (row & 7)) << 4)) = r[i];
+      *reinterpret_cast<u32x4*>(lds + row * 128 + ((c ^ (row & 7)) << 4)) = r[i];
     } else {
       constexpr int CPR = ROWS / 8;
       const int kr = id / CPR, c = id % CPR;
-      *reinterpret_cast<uint4*>(lds + kr * TileLds<ROWS, KC>::STRIDE_MC + c * 16) = r[i];
+      *reinterpret_cast<u32x4*>(lds + kr * TileLds<ROWS, KC>::STRIDE_MC + c * 16) = r[i];
     }
   }
 }
@@ -163,42 +214,109 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  uint4 ra[LA::NCHUNK], rb[LB::NCHUNK];
-  slab_load<BM, A_KC>(ra, A, lda, m0, 0);
-  slab_load<BN, B_KC>(rb, B, ldb, n0, 0);
-  slab_store<BM, A_KC>(ra, smem);
-  slab_store<BN, B_KC>(rb, smem + LA::BYTES);
+  const int nk = K / GK;
+  {
+    u32x4 ra[LA::NCHUNK], rb[LB::NCHUNK];
+    slab_load<BM, A_KC>(ra, A, lda, m0, 0);
+    slab_load<BN, B_KC>(rb, B, ldb, n0, 0);
+    slab_store<BM, A_KC>(ra, smem);
+    slab_store<BN, B_KC>(rb, smem + LA::BYTES);
+  }
+
+  // Staging registers for the slab after next, in three groups [0,G1) [G1,G2) [G2,NS); entries
+  // below NA belong to operand A.  Group g of slab kt+1 is written to LDS in phase g of
+  // iteration kt and its registers are refilled at once with group g of slab kt+2, so every
+  // load has a full iteration of MFMAs to arrive, and LDS writes come in small bursts between
+  // the fragment reads instead of one block.  Past the last slab the final one is requested
+  // again, which keeps the outstanding-load count (and the vmcnt arguments) uniform.
+  constexpr int NA = LA::NCHUNK, NS = LA::NCHUNK + LB::NCHUNK;
+  constexpr int G1 = (NS + 2) / 3, G2 = G1 + (NS - G1 + 1) / 2;
+  constexpr int C0 = G1, C1 = G2 - G1, C2 = NS - G2;
+  u32x4 rs[NS];
+  auto issue = [&](auto lo_c, auto hi_c, int k0) {
+#pragma unroll
+    for (int i = decltype(lo_c)::value; i < decltype(hi_c)::value; i++)
+      load_issue(rs[i], i < NA ? chunk_src<BM, A_KC>(A, lda, m0, k0, i) : chunk_src<BN, B_KC>(B, ldb, n0, k0, i - NA));
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, G1>;
+  using I2 = std::integral_constant<int, G2>;
+  using I3 = std::integral_constant<int, NS>;
+  {
+    const int k1 = min(1, nk - 1) * GK;
+    issue(I0{}, I1{}, k1);
+    issue(I1{}, I2{}, k1);
+    issue(I2{}, I3{}, k1);
+  }
   __syncthreads();
 
-  auto compute = [&](const char* curA, const char* curB) {
+  // Software pipeline.  A slab is four k-steps ("phases") of TM x TN MFMAs each.  Operand
+  // fragments are double buffered in registers: phase s issues the LDS reads for phase s+1.
+  // One barrier per slab, between phases 2 and 3: by then every wave has read its last
+  // fragments of the current slab and written its share of the next slab to the other buffer,
+  // so phase 3 already fetches the first fragments of the next slab.
+  //
+  // With one wave per SIMD nothing else can fill the matrix core while this wave issues its
+  // loads and stores, so every other instruction is slotted between two MFMAs: slot t of a
+  // phase follows MFMA t and holds at most one fragment read, one LDS write and one global
+  // load.  sched_barrier after each slot keeps the compiler from regrouping them.
+  static_assert(GK / 16 == 4, "pipeline below is written for four k-steps per slab");
+  constexpr int NSLOT = TM * TN;
+  static_assert(TM + TN <= NSLOT && C0 <= NSLOT, "slots per phase");
+  bf16x8 fa[2][TM], fb[2][TN];
+  // MFMA t of the phase running on fragment buffer `use`, then slot t: fragment read t of k-step
+  // ks from slab `src` into buffer use ^ 1 (when LOADF), and staged chunk LO + t - S0 (when in
+  // range): written to `dst`, then refilled from global k offset k2.
+  auto phase = [&](auto use_c, auto loadf_c, const char* src, int ks, auto lo_c, auto hi_c, auto vm_c, char* dst,
+                   int k2) {
+    constexpr int USE = decltype(use_c)::value, LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
+    constexpr bool LOADF = decltype(loadf_c)::value;
+    constexpr int S0 = NSLOT - (HI - LO);
 #pragma unroll
-    for (int ks = 0; ks < GK / 16; ks++) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) fa[i] = frag_load<BM, A_KC>(curA, wm + i * 32, ks, lane);
-#pragma unroll
-      for (int j = 0; j < TN; j++) fb[j] = frag_load<BN, B_KC>(curB, wn + j * 32, ks, lane);
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    for (int t = 0; t < NSLOT; t++) {
+      const int i = t / TN, j = t % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[USE][i], fb[USE][j], acc[i][j], 0, 0, 0);
+      if (LOADF) {
+        if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(src, wm + t * 32, ks, lane);
+        else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(src + LA::BYTES, wn + (t - TM) * 32, ks, lane);
+      }
+      if (HI > LO) {
+        if (t == S0) stage_wait<LO, (HI > LO ? HI : LO + 1), decltype(vm_c)::value>(rs);
+        if (t >= S0) {
+          const int c = LO + t - S0;
+          *reinterpret_cast<u32x4*>(dst + (c < NA ? chunk_dst<BM, A_KC>(c) : LA::BYTES + chunk_dst<BN, B_KC>(c - NA))) = rs[c];
+          load_issue(rs[c], c < NA ? chunk_src<BM, A_KC>(A, lda, m0, k2, c) : chunk_src<BN, B_KC>(B, ldb, n0, k2, c - NA));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
+  using Z = std::integral_constant<int, 0>;
+  using One = std::integral_constant<int, 1>;
+  using T_ = std::true_type;
+  using F_ = std::false_type;
 
-  const int nk = K / GK;
+#pragma unroll
+  for (int i = 0; i < TM; i++) fa[0][i] = frag_load<BM, A_KC>(smem, wm + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; j++) fb[0][j] = frag_load<BN, B_KC>(smem + LA::BYTES, wn + j * 32, 0, lane);
   for (int kt = 0; kt < nk - 1; kt++) {
-    const char* curA = smem + (kt & 1) * STAGE;
-    char* nxtA = smem + ((kt + 1) & 1) * STAGE;
-    slab_load<BM, A_KC>(ra, A, lda, m0, (kt + 1) * GK);
-    slab_load<BN, B_KC>(rb, B, ldb, n0, (kt + 1) * GK);
-    compute(curA, curA + LA::BYTES);
-    slab_store<BM, A_KC>(ra, nxtA);
-    slab_store<BN, B_KC>(rb, nxtA + LA::BYTES);
+    const char* cur = smem + (kt & 1) * STAGE;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    const int k2 = min(kt + 2, nk - 1) * GK;
+    phase(Z{}, T_{}, cur, 1, I0{}, I1{}, std::integral_constant<int, C1 + C2>{}, nxt, k2);
+    phase(One{}, T_{}, cur, 2, I1{}, I2{}, std::integral_constant<int, C2 + C0>{}, nxt, k2);
+    phase(Z{}, T_{}, cur, 3, I2{}, I3{}, std::integral_constant<int, C0 + C1>{}, nxt, k2);
     __syncthreads();
+    phase(One{}, T_{}, nxt, 0, Z{}, Z{}, Z{}, nxt, 0);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-requested last slab: drain before the registers die
   {
-    const char* curA = smem + ((nk - 1) & 1) * STAGE;
-    compute(curA, curA + LA::BYTES);
+    const char* cur = smem + ((nk - 1) & 1) * STAGE;
+    phase(Z{}, T_{}, cur, 1, Z{}, Z{}, Z{}, nullptr, 0);
+    phase(One{}, T_{}, cur, 2, Z{}, Z{}, Z{}, nullptr, 0);
+    phase(Z{}, T_{}, cur, 3, Z{}, Z{}, Z{}, nullptr, 0);
+    phase(One{}, F_{}, cur, 0, Z{}, Z{}, Z{}, nullptr, 0);
   }
 
 #pragma unroll
