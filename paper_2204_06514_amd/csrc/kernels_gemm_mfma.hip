@@ -75,7 +75,9 @@ __device__ __forceinline__ int chunk_dst(int i) {
 // exposes the global-memory latency once per slab.  A volatile asm statement keeps its place;
 // in exchange the wait is explicit: stage_wait<LO, HI, VM>() lets all but the VM most recent
 // loads finish (loads return in order) and takes registers LO..HI-1 as in/out operands, so
-// every later use of them depends on the wait.
+// every later use of them depends on the wait.  Every register that load_issue() has written
+// MUST reach a stage_wait() on every path, also when its value is never used: the operand is
+// what keeps the register reserved while the load is in flight.
 __device__ __forceinline__ void load_issue(u32x4& r, const bf16_t* src) {
   asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(r) : "v"(src) : "memory");
 }
@@ -175,6 +177,50 @@ __device__ __forceinline__ void mfma_epilogue(const EpiArgs& e, int m, int n, fl
     acc *= EM == EM_DGELU_TANH ? gelu_tanh_grad_fast(u) : gelu_grad_f(u, FAX_GELU_ERF);
   }
   ((bf16_t*)e.C)[(size_t)m * e.ldc + n] = (bf16_t)acc;
+}
+
+// Four consecutive columns n..n+3 of row m at once: 8-byte bf16 loads and stores.
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+__device__ __forceinline__ float4 ld_bf16x4(const void* base, size_t idx) {
+  const bf16x4 v = *reinterpret_cast<const bf16x4*>((const bf16_t*)base + idx);
+  return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+}
+__device__ __forceinline__ void st_bf16x4(void* base, size_t idx, float4 a) {
+  bf16x4 v;
+  v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
+  *reinterpret_cast<bf16x4*>((bf16_t*)base + idx) = v;
+}
+template <int EM>
+__device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, float4 a, float4 bias) {
+  if (EM == EM_STORE && e.C2) st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, a);
+  a.x += bias.x; a.y += bias.y; a.z += bias.z; a.w += bias.w;
+  if (e.R) {
+    const float4 r = ld_bf16x4(e.R, (size_t)m * e.ldr + n);
+    a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+  }
+  if (EM == EM_GELU_TANH || EM == EM_GELU_ERF) {
+    st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
+    float4 g;
+    if (EM == EM_GELU_TANH) {
+      g = make_float4(gelu_tanh_fast(a.x), gelu_tanh_fast(a.y), gelu_tanh_fast(a.z), gelu_tanh_fast(a.w));
+    } else {
+      g = make_float4(gelu_f(a.x, FAX_GELU_ERF), gelu_f(a.y, FAX_GELU_ERF), gelu_f(a.z, FAX_GELU_ERF),
+                      gelu_f(a.w, FAX_GELU_ERF));
+    }
+    st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, g);
+    return;
+  }
+  if (EM == EM_DGELU_TANH || EM == EM_DGELU_ERF) {
+    const float4 u = ld_bf16x4(e.U, (size_t)m * e.ldu + n);
+    if (EM == EM_DGELU_TANH) {
+      a.x *= gelu_tanh_grad_fast(u.x); a.y *= gelu_tanh_grad_fast(u.y);
+      a.z *= gelu_tanh_grad_fast(u.z); a.w *= gelu_tanh_grad_fast(u.w);
+    } else {
+      a.x *= gelu_grad_f(u.x, FAX_GELU_ERF); a.y *= gelu_grad_f(u.y, FAX_GELU_ERF);
+      a.z *= gelu_grad_f(u.z, FAX_GELU_ERF); a.w *= gelu_grad_f(u.w, FAX_GELU_ERF);
+    }
+  }
+  st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
 }
 
 template <int BM, int BN, bool A_KC, bool B_KC, int EM>
@@ -310,7 +356,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     __syncthreads();
     phase(One{}, T_{}, nxt, 0, Z{}, Z{}, Z{}, nxt, 0);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-requested last slab: drain before the registers die
+  // Drain the re-requested last slab.  The staging registers are operands of the waits so that
+  // they stay allocated until the loads have landed: a register the compiler considers dead
+  // while a load into it is still in flight would be handed to something else and clobbered.
+  stage_wait<0, G1, 0>(rs);
+  stage_wait<G1, G2, 0>(rs);
+  stage_wait<G2, NS, 0>(rs);
   {
     const char* cur = smem + ((nk - 1) & 1) * STAGE;
     phase(Z{}, T_{}, cur, 1, Z{}, Z{}, Z{}, nullptr, 0);
@@ -319,17 +370,57 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     phase(One{}, F_{}, cur, 0, Z{}, Z{}, Z{}, nullptr, 0);
   }
 
+  if constexpr (EM == EM_F32) {
+    // fp32 output: 32 consecutive lanes already cover 128 contiguous bytes of a row
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+    for (int i = 0; i < TM; i++)
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
+      for (int j = 0; j < TN; j++) {
+        const int n = n0 + wn + j * 32 + (lane & 31);
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int m = m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        mfma_epilogue<EM>(e, m, n, acc[i][j][v]);
+        for (int v = 0; v < 16; v++) {
+          const int m = m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          mfma_epilogue<EM>(e, m, n, acc[i][j][v]);
+        }
       }
+  } else {
+    // bf16 outputs: an accumulator register holds one column of four different rows, which would
+    // mean 2-byte stores scattered over rows.  Each wave instead turns 64 rows of its tile at a
+    // time through its own quarter of LDS (fp32) and reads them back row-wise, four consecutive
+    // columns per lane, so bias, residual and the GELU side inputs move as 8-byte vectors and a
+    // row of the wave tile leaves as one contiguous run.
+    constexpr int WC = TN * 32;   // columns of the wave tile
+    constexpr int LPR = WC / 4;   // lanes per row on the way out
+    constexpr int RPI = 64 / LPR; // rows per store instruction
+    __syncthreads();              // every wave is done with the operand slabs
+    float* wbuf = reinterpret_cast<float*>(smem) + wave * 64 * WC;
+    const int c4 = (lane % LPR) * 4;
+    const int ncol = n0 + wn + c4;
+    float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (e.bias) bias = ld_bf16x4(e.bias, ncol);
+#pragma unroll
+    for (int half = 0; half < TM / 2; half++) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ii++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+#pragma unroll
+          for (int v = 0; v < 16; v++)
+            wbuf[(ii * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * WC + j * 32 + (lane & 31)] = acc[half * 2 + ii][j][v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 4
+      for (int k = 0; k < 64 / RPI; k++) {
+        const int row = k * RPI + lane / LPR;
+        const float4 a = *reinterpret_cast<const float4*>(wbuf + row * WC + c4);
+        mfma_epilogue4<EM>(e, m0 + wm + half * 64 + row, ncol, a, bias);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
+  }
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -349,6 +440,11 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.epi == EPI_DGELU && (g.ta || !g.tb)) return false;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % GK != 0) return false;
   if (g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return false;
+  if (!g.c_f32) {  // the bf16 epilogue moves four columns at a time
+    auto vec_ok = [](const void* p, int ld) { return !p || (ld % 4 == 0 && (reinterpret_cast<uintptr_t>(p) & 7) == 0); };
+    if (!vec_ok(g.C, g.ldc) || !vec_ok(g.C2, g.ldc2) || !vec_ok(g.R, g.ldr) || !vec_ok(g.U, g.ldu) || !vec_ok(g.bias, 4))
+      return false;
+  }
   return pick_tile(g) != 0;
 }
 
