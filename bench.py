@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="first run a plain elementwise copy kernel (reads 256 MiB, writes 128 MiB): a known-size reference "
+                         "for the HBM byte counters")
     return ap.parse_args()
 
 
@@ -130,6 +133,15 @@ def main():
         flops_full = sh.L * sh.block_flops_fwd_bwd(False)
         what = "%d x (fax_block_fwd + fax_block_bwd)%s" % (sh.L, " + fax_adamw_step on every tensor" if with_adam else "")
 
+    if args.calib_copy:
+        # an elementwise fp32 -> bf16 copy: reads exactly 2^28 bytes, writes exactly 2^27
+        src = torch.zeros(1 << 26, dtype=torch.float32, device=dev)
+        dst = torch.empty(1 << 26, dtype=torch.bfloat16, device=dev)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -162,6 +174,7 @@ def main():
                 "launches_per_step": dom["launches"] // args.steps,
                 "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
                 "bytes_per_launch_avg": dom["work"] / dom["launches"]}
+    roof["traffic"] = committed_traffic(args.config, dom["name"])
     kernels = []
     for r in rows:
         per_step_ms = r["ms"] / args.steps
@@ -190,6 +203,20 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+def committed_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by the copy-kernel calibration stated there), or None if not recorded."""
+    import re
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % config)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"^%s\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel), line)
+        if m:
+            return float(m.group(1))
+    return None
 
 
 def cpu_baseline(name, cfg):

