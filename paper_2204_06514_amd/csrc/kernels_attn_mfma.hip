@@ -64,6 +64,26 @@ __device__ __forceinline__ void tile_store(const uint4 (&r)[DH / 32], char* lds)
   }
 }
 
+// The same tile moved global -> LDS directly (global_load_lds_dwordx4: no staging registers, no
+// LDS store instructions).  One wave instruction fills 1024 consecutive LDS bytes, lane i at
+// +16 i, so the swizzle is applied on the global side: the lane that owns physical chunk p of
+// row r fetches logical chunk p ^ f(r).  The data is in LDS once vmcnt has drained, which the
+// next __syncthreads() (a workgroup fence) waits for.
+template <int DH>
+__device__ __forceinline__ void tile_dma(char* lds, const bf16_t* __restrict__ src, size_t ld) {
+  constexpr int NCH = DH / 8;         // 16-byte chunks per row
+  constexpr int RPI = 64 / NCH;       // rows per wave instruction
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < DH / 32; i++) {
+    const int seg = wave * (DH / 32) + i;  // which 1 KB segment of the tile
+    const int row = seg * RPI + lane / NCH;
+    const int chunk = (lane % NCH) ^ swz(row);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (size_t)row * ld + chunk * 8),
+                                     (__attribute__((address_space(3))) void*)(lds + seg * 1024), 16, 0, 0);
+  }
+}
+
 // A operand, rows rb..rb+31 of the tile, contraction over the tile's columns (k-step ks).
 template <int DH>
 __device__ __forceinline__ bf16x8 frag_rows(const char* lds, int rb, int ks, int lane) {
@@ -115,7 +135,7 @@ __device__ __forceinline__ void store_rows(bf16_t* __restrict__ dst, const f32x1
 // Forward.  grid (S/128, B*H); wave w owns queries 128 qt + 32 w .. + 31; 64-key tiles.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ ctx, float* __restrict__ lse) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 x [K tile | V tile]
@@ -151,27 +171,35 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, const 
       for (int ks = 0; ks < KS; ks++)
         s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(kt, jt * 32, ks, lane), qf[ks], s[jt], 0, 0, 0);
     }
+    // Scores stay unscaled; the softmax scale rides in the exponent: p = 2^(c s - c m), c = scale log2 e.
     const bool diag = j0 + 63 > q0w;
+    const float c = scale * LOG2E;
     float mx = -INFINITY;
+    if (diag) {
 #pragma unroll
-    for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int key = j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-        float val = s[jt][v] * scale;
-        if (diag && key > iq) val = -INFINITY;
-        s[jt][v] = val;
-        mx = fmaxf(mx, val);
-      }
+        for (int v = 0; v < 16; v++) {
+          const int key = j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+          if (key > iq) s[jt][v] = -INFINITY;
+          mx = fmaxf(mx, s[jt][v]);
+        }
+    } else {
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[jt][v]);
+    }
     mx = fmaxf(mx, xor32(mx));
     const float mn = fmaxf(m, mx);  // finite: key j0 <= q0w is visible to every query of the wave
-    const float corr = __builtin_amdgcn_exp2f((m - mn) * LOG2E);
+    const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
+    const float mc = mn * c;
     float rs = 0.f;
 #pragma unroll
     for (int jt = 0; jt < 2; jt++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        const float p = __builtin_amdgcn_exp2f((s[jt][v] - mn) * LOG2E);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[jt][v], c, -mc));
         s[jt][v] = p;
         rs += p;
       }
@@ -195,20 +223,15 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, const 
   };
 
   const int n_kv = 2 * (qt + 1);
-  uint4 rk[DH / 32], rv[DH / 32];
-  tile_load<DH>(rk, base + Hd, ld);
-  tile_load<DH>(rv, base + 2 * Hd, ld);
-  tile_store<DH>(rk, smem);
-  tile_store<DH>(rv, smem + TB);
+  tile_dma<DH>(smem, base + Hd, ld);
+  tile_dma<DH>(smem + TB, base + 2 * Hd, ld);
   __syncthreads();
   for (int t = 0; t < n_kv - 1; t++) {
     const char* cur = smem + (t & 1) * 2 * TB;
     char* nxt = smem + ((t + 1) & 1) * 2 * TB;
-    tile_load<DH>(rk, base + (size_t)(t + 1) * TR * ld + Hd, ld);
-    tile_load<DH>(rv, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
+    tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
+    tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
     step(cur, cur + TB, t * TR);
-    tile_store<DH>(rk, nxt);
-    tile_store<DH>(rv, nxt + TB);
     __syncthreads();
   }
   {
@@ -217,14 +240,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, const 
   }
 
   store_rows<DH>(ctx + ((size_t)b * S + iq) * Hd + h * DH, oacc, 1.f / l, g);
-  if (g == 0) lse[((size_t)b * H + h) * S + iq] = m + logf(l);
+  if (g == 0) lse[((size_t)b * H + h) * S + iq] = m * scale + logf(l);
 }
 
 // ---------------------------------------------------------------------------------------------
 // dQ.  Same decomposition as the forward pass; K and V tiles in LDS.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta,
                                                                const bf16_t* __restrict__ dctx,
@@ -292,20 +315,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, con
   };
 
   const int n_kv = 2 * (qt + 1);
-  uint4 rk[DH / 32], rv[DH / 32];
-  tile_load<DH>(rk, base + Hd, ld);
-  tile_load<DH>(rv, base + 2 * Hd, ld);
-  tile_store<DH>(rk, smem);
-  tile_store<DH>(rv, smem + TB);
+  tile_dma<DH>(smem, base + Hd, ld);
+  tile_dma<DH>(smem + TB, base + 2 * Hd, ld);
   __syncthreads();
   for (int t = 0; t < n_kv - 1; t++) {
     const char* cur = smem + (t & 1) * 2 * TB;
     char* nxt = smem + ((t + 1) & 1) * 2 * TB;
-    tile_load<DH>(rk, base + (size_t)(t + 1) * TR * ld + Hd, ld);
-    tile_load<DH>(rv, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
+    tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
+    tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
     step(cur, cur + TB, t * TR);
-    tile_store<DH>(rk, nxt);
-    tile_store<DH>(rv, nxt + TB);
     __syncthreads();
   }
   {
@@ -352,42 +370,38 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, co
 #pragma unroll
     for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
 
+  // One 64-query tile, as two halves of 32 so that only one half's scores are live at a time.
   auto step = [&](const char* qt_, const char* dot_, const float* ls, const float* ds_, int i0) {
     if (i0 + 63 < j0w) return;  // every query of this tile precedes this wave's keys
-    f32x16 s[2], dp[2];
-#pragma unroll
-    for (int it = 0; it < 2; it++) {
-#pragma unroll
-      for (int v = 0; v < 16; v++) s[it][v] = dp[it][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        s[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(qt_, it * 32, ks, lane), kf[ks], s[it], 0, 0, 0);
-        dp[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(dot_, it * 32, ks, lane), vf[ks], dp[it], 0, 0, 0);
-      }
-    }
     const bool diag = i0 < j0w + 31;
 #pragma unroll
-    for (int it = 0; it < 2; it++)
+    for (int it = 0; it < 2; it++) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int v = 0; v < 16; v++) s[v] = dp[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(qt_, it * 32, ks, lane), kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(dot_, it * 32, ks, lane), vf[ks], dp, 0, 0, 0);
+      }
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const int r0 = it * 32 + q * 8 + g * 4;
-        const float4 l4 = *reinterpret_cast<const float4*>(ls + r0);
+        const float4 l4 = *reinterpret_cast<const float4*>(ls + r0);   // lse * log2(e), pre-scaled on the way in
         const float4 d4 = *reinterpret_cast<const float4*>(ds_ + r0);
         const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int r = 0; r < 4; r++) {
           const int v = q * 4 + r;
-          float p = __builtin_amdgcn_exp2f(s[it][v] * (scale * LOG2E) - lv[r] * LOG2E);
+          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale * LOG2E, -lv[r]));
           if (diag && jk > i0 + r0 + r) p = 0.f;
-          s[it][v] = p;
-          dp[it][v] = p * (dp[it][v] - dvv[r]);
+          s[v] = p;
+          dp[v] = p * (dp[v] - dvv[r]);
         }
       }
 #pragma unroll
-    for (int it = 0; it < 2; it++)
-#pragma unroll
       for (int hh = 0; hh < 2; hh++) {
-        const bf16x8 pb = pack8(s[it], hh), db = pack8(dp[it], hh);
+        const bf16x8 pb = pack8(s, hh), db = pack8(dp, hh);
 #pragma unroll
         for (int dt = 0; dt < DT; dt++) {
           dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(dot_, dt * 32, it * 32 + hh * 16, lane), pb,
@@ -396,35 +410,33 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, co
                                                            dk[dt], 0, 0, 0);
         }
       }
+    }
   };
 
   const int i_first = kt * 128;
   const int n_q = (S - i_first) / TR;
-  uint4 rq[DH / 32], rd[DH / 32];
   float rl = 0.f, rdl = 0.f;
-  auto load = [&](int i0) {
-    tile_load<DH>(rq, base + (size_t)i0 * ld, ld);
-    tile_load<DH>(rd, dob + (size_t)i0 * Hd, (size_t)Hd);
+  auto load = [&](int i0, char* st) {
+    tile_dma<DH>(st, base + (size_t)i0 * ld, ld);
+    tile_dma<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd);
     if (threadIdx.x < TR) {
-      rl = lrow[i0 + threadIdx.x];
+      rl = lrow[i0 + threadIdx.x] * LOG2E;
       rdl = drow[i0 + threadIdx.x];
     }
   };
   auto store = [&](char* st) {
-    tile_store<DH>(rq, st);
-    tile_store<DH>(rd, st + TB);
     if (threadIdx.x < TR) {
       reinterpret_cast<float*>(st + 2 * TB)[threadIdx.x] = rl;
       reinterpret_cast<float*>(st + 2 * TB + TR * 4)[threadIdx.x] = rdl;
     }
   };
-  load(i_first);
+  load(i_first, smem);
   store(smem);
   __syncthreads();
   for (int t = 0; t < n_q - 1; t++) {
     const char* cur = smem + (t & 1) * STAGE;
     char* nxt = smem + ((t + 1) & 1) * STAGE;
-    load(i_first + (t + 1) * TR);
+    load(i_first + (t + 1) * TR, nxt);
     step(cur, cur + TB, reinterpret_cast<const float*>(cur + 2 * TB), reinterpret_cast<const float*>(cur + 2 * TB + TR * 4),
          i_first + t * TR);
     store(nxt);
