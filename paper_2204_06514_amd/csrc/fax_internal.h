@@ -167,6 +167,24 @@ __device__ __forceinline__ float gelu_grad_f(float u, int form) {
   float pdf = 0.3989422804014327f * expf(-0.5f * u * u);
   return cdf + u * pdf;
 }
+// ---- direct global -> LDS loads ---------------------------------------------------------------
+// global_load_lds_dwordx4: each lane names 16 bytes of global memory; the wave's 1024 bytes land
+// in LDS at M0 + 16 * lane.  No destination registers and no LDS store instructions.  Issued
+// through inline assembly because the compiler, given the builtin, waits for every outstanding
+// load of this kind before each later LDS read that it cannot prove disjoint -- here all of them,
+// which would expose the full memory latency.  In exchange the completion wait is explicit:
+// lds_dma_wait() (vmcnt drains when the data is in LDS) must precede the barrier that publishes
+// the buffer.  `lds_segment` must be wave-uniform.  M0 is not otherwise used by these kernels.
+// lds_addr(): the 32-bit LDS address of a pointer into shared memory (take it once per kernel).
+__device__ __forceinline__ unsigned lds_addr(const void* shared_ptr) {
+  return (unsigned)(__UINTPTR_TYPE__)(__attribute__((address_space(3))) const char*)shared_ptr;
+}
+__device__ __forceinline__ void lds_dma16(const void* global_src, unsigned lds_segment_addr) {
+  const unsigned dst = __builtin_amdgcn_readfirstlane(lds_segment_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(global_src) : "memory");
+}
+__device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // ---- GEMM epilogue shared by the scalar and MFMA kernels ----
 struct EpiArgs {
   const void* bias;

@@ -44,33 +44,13 @@ __device__ __forceinline__ int tile_off(int row, int chunk) {
   return row * (DH * 2) + ((chunk ^ swz(row)) << 4);
 }
 
-// 64 x DH tile: global rows (row-major, leading dimension ld elements) -> registers -> LDS.
-template <int DH>
-__device__ __forceinline__ void tile_load(uint4 (&r)[DH / 32], const bf16_t* __restrict__ src, size_t ld) {
-  constexpr int NCH = DH / 8;
-#pragma unroll
-  for (int i = 0; i < DH / 32; i++) {
-    const int id = threadIdx.x + i * 256;
-    r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(id / NCH) * ld + (id % NCH) * 8);
-  }
-}
-template <int DH>
-__device__ __forceinline__ void tile_store(const uint4 (&r)[DH / 32], char* lds) {
-  constexpr int NCH = DH / 8;
-#pragma unroll
-  for (int i = 0; i < DH / 32; i++) {
-    const int id = threadIdx.x + i * 256;
-    *reinterpret_cast<uint4*>(lds + tile_off<DH>(id / NCH, id % NCH)) = r[i];
-  }
-}
-
-// The same tile moved global -> LDS directly (global_load_lds_dwordx4: no staging registers, no
+// A 64 x DH tile moved global -> LDS directly (global_load_lds_dwordx4: no staging registers, no
 // LDS store instructions).  One wave instruction fills 1024 consecutive LDS bytes, lane i at
 // +16 i, so the swizzle is applied on the global side: the lane that owns physical chunk p of
-// row r fetches logical chunk p ^ f(r).  The data is in LDS once vmcnt has drained, which the
-// next __syncthreads() (a workgroup fence) waits for.
+// row r fetches logical chunk p ^ f(r).  lds_dma_wait() must precede the barrier that publishes
+// the tile.
 template <int DH>
-__device__ __forceinline__ void tile_dma(char* lds, const bf16_t* __restrict__ src, size_t ld) {
+__device__ __forceinline__ void tile_dma(unsigned lds, const bf16_t* __restrict__ src, size_t ld) {
   constexpr int NCH = DH / 8;         // 16-byte chunks per row
   constexpr int RPI = 64 / NCH;       // rows per wave instruction
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -79,8 +59,7 @@ __device__ __forceinline__ void tile_dma(char* lds, const bf16_t* __restrict__ s
     const int seg = wave * (DH / 32) + i;  // which 1 KB segment of the tile
     const int row = seg * RPI + lane / NCH;
     const int chunk = (lane % NCH) ^ swz(row);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (size_t)row * ld + chunk * 8),
-                                     (__attribute__((address_space(3))) void*)(lds + seg * 1024), 16, 0, 0);
+    lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
   }
 }
 
@@ -223,16 +202,19 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, con
   };
 
   const int n_kv = 2 * (qt + 1);
-  tile_dma<DH>(smem, base + Hd, ld);
-  tile_dma<DH>(smem + TB, base + 2 * Hd, ld);
+  const unsigned sm = lds_addr(smem);
+  tile_dma<DH>(sm, base + Hd, ld);
+  tile_dma<DH>(sm + TB, base + 2 * Hd, ld);
+  lds_dma_wait();
   __syncthreads();
   for (int t = 0; t < n_kv - 1; t++) {
     const char* cur = smem + (t & 1) * 2 * TB;
-    char* nxt = smem + ((t + 1) & 1) * 2 * TB;
+    const unsigned nxt = sm + ((t + 1) & 1) * 2 * TB;
     tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
     tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
     step(cur, cur + TB, t * TR);
-    __syncthreads();
+    lds_dma_wait();
+  __syncthreads();
   }
   {
     const char* cur = smem + ((n_kv - 1) & 1) * 2 * TB;
@@ -315,16 +297,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
   };
 
   const int n_kv = 2 * (qt + 1);
-  tile_dma<DH>(smem, base + Hd, ld);
-  tile_dma<DH>(smem + TB, base + 2 * Hd, ld);
+  const unsigned sm = lds_addr(smem);
+  tile_dma<DH>(sm, base + Hd, ld);
+  tile_dma<DH>(sm + TB, base + 2 * Hd, ld);
+  lds_dma_wait();
   __syncthreads();
   for (int t = 0; t < n_kv - 1; t++) {
     const char* cur = smem + (t & 1) * 2 * TB;
-    char* nxt = smem + ((t + 1) & 1) * 2 * TB;
+    const unsigned nxt = sm + ((t + 1) & 1) * 2 * TB;
     tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
     tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
     step(cur, cur + TB, t * TR);
-    __syncthreads();
+    lds_dma_wait();
+  __syncthreads();
   }
   {
     const char* cur = smem + ((n_kv - 1) & 1) * 2 * TB;
@@ -416,9 +401,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, co
   const int i_first = kt * 128;
   const int n_q = (S - i_first) / TR;
   float rl = 0.f, rdl = 0.f;
-  auto load = [&](int i0, char* st) {
-    tile_dma<DH>(st, base + (size_t)i0 * ld, ld);
-    tile_dma<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd);
+  const unsigned sm = lds_addr(smem);
+  auto load = [&](int i0, int buf) {
+    tile_dma<DH>(sm + buf * STAGE, base + (size_t)i0 * ld, ld);
+    tile_dma<DH>(sm + buf * STAGE + TB, dob + (size_t)i0 * Hd, (size_t)Hd);
     if (threadIdx.x < TR) {
       rl = lrow[i0 + threadIdx.x] * LOG2E;
       rdl = drow[i0 + threadIdx.x];
@@ -430,17 +416,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, co
       reinterpret_cast<float*>(st + 2 * TB + TR * 4)[threadIdx.x] = rdl;
     }
   };
-  load(i_first, smem);
+  load(i_first, 0);
   store(smem);
+  lds_dma_wait();
   __syncthreads();
   for (int t = 0; t < n_q - 1; t++) {
     const char* cur = smem + (t & 1) * STAGE;
     char* nxt = smem + ((t + 1) & 1) * STAGE;
-    load(i_first + (t + 1) * TR, nxt);
+    load(i_first + (t + 1) * TR, (t + 1) & 1);
     step(cur, cur + TB, reinterpret_cast<const float*>(cur + 2 * TB), reinterpret_cast<const float*>(cur + 2 * TB + TR * 4),
          i_first + t * TR);
     store(nxt);
-    __syncthreads();
+    lds_dma_wait();
+  __syncthreads();
   }
   {
     const char* cur = smem + ((n_q - 1) & 1) * STAGE;

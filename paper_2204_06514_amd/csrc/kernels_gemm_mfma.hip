@@ -1,16 +1,20 @@
 // bf16 GEMM on the CDNA4 matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulate.
 //
 // One 256-thread workgroup (4 wavefronts, 2x2) computes a BM x BN tile of C, stepping over K in
-// slabs of 64.  Each slab of A and of B is staged through LDS, double buffered: global loads of
-// slab k+1 are issued before the MFMAs of slab k and parked in registers meanwhile.
+// slabs of 64.  Slabs of A and B go from global memory straight into LDS
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), double buffered,
+// each requested a full slab of MFMAs before it is needed.
 //
 // An operand whose contraction index is contiguous in memory ("KC": A stored [M,K], B stored
 // [N,K]) is kept in LDS as [row][64] with the 16-byte chunk index XOR-ed with (row & 7), so
 // that the 128-bit fragment reads of 8 consecutive rows fall in 8 different bank groups.
 // An operand whose M/N index is contiguous ("MC": A stored [K,M], B stored [K,N]) is kept as
-// [k][rows + 16] and fetched with ds_read_b64_tr_b16, the LDS transpose read: 16 lanes pick up
-// four k-rows x 16 columns and each lane receives 4 consecutive k for its own column; two such
-// reads make one MFMA operand.  The 32-byte row padding spreads the four k-rows over all banks.
+// [k][rows] and fetched with ds_read_b64_tr_b16, the LDS transpose read: 16 lanes pick up four
+// k-rows x 16 columns and each lane receives 4 consecutive k for its own column; two such reads
+// make one MFMA operand.  There the 32-byte column-group index is XOR-ed with (k & 3), which
+// spreads the four k-rows of one read over all banks.  A direct-to-LDS load writes 1024
+// consecutive LDS bytes per wave instruction (lane i at +16 i), so both swizzles are applied on
+// the global side: each lane fetches the chunk that belongs at its LDS position.
 //
 // MFMA 32x32x16 lane layout (lane l): A/B operand = row/column (l & 31), k = 8 (l >> 5) + 0..7;
 // accumulator v = 0..15 holds C[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
@@ -24,100 +28,27 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;  // 16 bytes in four consecutive VGPRs
 
 static constexpr int GK = 64;  // K slab
 
 template <int ROWS, bool KC>
 struct TileLds {
-  static constexpr int STRIDE_MC = (ROWS + 16) * 2;  // bytes per k-row, MC layout
-  static constexpr int BYTES = KC ? ROWS * 128 : GK * STRIDE_MC;
-  static constexpr int NCHUNK = ROWS * GK / 8 / 256;  // 16-byte chunks per thread per slab
+  static constexpr int BYTES = ROWS * GK * 2;
+  static constexpr int NSEG = BYTES / 1024 / 4;  // 1 KB segments (= load instructions) per wave per slab
 };
 
-// Global -> registers for one slab of one operand.
+// Global address of the 16 bytes that belong at LDS byte offset `b` of the slab starting at
+// (row0, k0).  Inverse of the layouts that frag_load() reads.
 template <int ROWS, bool KC>
-__device__ __forceinline__ void slab_load(u32x4 (&r)[ROWS * GK / 8 / 256], const bf16_t* __restrict__ P, int ld,
-                                          int row0, int k0) {
-#pragma unroll
-  for (int i = 0; i < TileLds<ROWS, KC>::NCHUNK; i++) {
-    const int id = threadIdx.x + i * 256;
-    if (KC) {
-      const int row = id >> 3, c = id & 7;
-      r[i] = *reinterpret_cast<const u32x4*>(P + (size_t)(row0 + row) * ld + k0 + c * 8);
-    } else {
-      constexpr int CPR = ROWS / 8;
-      const int kr = id / CPR, c = id % CPR;
-      r[i] = *reinterpret_cast<const u32x4*>(P + (size_t)(k0 + kr) * ld + row0 + c * 8);
-    }
+__device__ __forceinline__ const bf16_t* slab_src(const bf16_t* __restrict__ P, int ld, int row0, int k0, int b) {
+  if (KC) {
+    const int row = b >> 7, pc = (b >> 4) & 7;
+    return P + (size_t)(row0 + row) * ld + k0 + ((pc ^ (row & 7)) << 3);
   }
-}
-
-// Per-chunk versions of the two functions below, used by the pipelined main loop: chunk i of a
-// slab is the 16 bytes that thread t moves, id = t + 256 i.
-template <int ROWS, bool KC>
-__device__ __forceinline__ const bf16_t* chunk_src(const bf16_t* __restrict__ P, int ld, int row0, int k0, int i) {
-  const int id = threadIdx.x + i * 256;
-  if (KC) return P + (size_t)(row0 + (id >> 3)) * ld + k0 + (id & 7) * 8;
-  constexpr int CPR = ROWS / 8;
-  return P + (size_t)(k0 + id / CPR) * ld + row0 + (id % CPR) * 8;
-}
-template <int ROWS, bool KC>
-__device__ __forceinline__ int chunk_dst(int i) {
-  const int id = threadIdx.x + i * 256;
-  if (KC) return (id >> 3) * 128 + (((id & 7) ^ ((id >> 3) & 7)) << 4);
-  constexpr int CPR = ROWS / 8;
-  return (id / CPR) * TileLds<ROWS, KC>::STRIDE_MC + (id % CPR) * 16;
-}
-
-// Global loads issued through inline assembly.  The optimiser treats a plain load as free to
-// sink next to its first use, which here is an LDS store a whole loop iteration later, and that
-// exposes the global-memory latency once per slab.  A volatile asm statement keeps its place;
-// in exchange the wait is explicit: stage_wait<LO, HI, VM>() lets all but the VM most recent
-// loads finish (loads return in order) and takes registers LO..HI-1 as in/out operands, so
-// every later use of them depends on the wait.  Every register that load_issue() has written
-// MUST reach a stage_wait() on every path, also when its value is never used: the operand is
-// what keeps the register reserved while the load is in flight.
-__device__ __forceinline__ void load_issue(u32x4& r, const bf16_t* src) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(r) : "v"(src) : "memory");
-}
-template <int LO, int HI, int VM, int NS>
-__device__ __forceinline__ void stage_wait(u32x4 (&r)[NS]) {
-  constexpr int C = HI - LO;
-  static_assert(C >= 1 && C <= 6 && HI <= NS, "chunk group size");
-  if constexpr (C == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r[LO]) : "n"(VM) : "memory");
-  if constexpr (C == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(r[LO]), "+v"(r[LO + 1]) : "n"(VM) : "memory");
-  if constexpr (C == 3)
-    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]) : "n"(VM) : "memory");
-  if constexpr (C == 4)
-    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]) : "n"(VM) : "memory");
-  if constexpr (C == 5)
-    asm volatile("s_waitcnt vmcnt(%5)"
-                 : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]), "+v"(r[LO + 4])
-                 : "n"(VM)
-                 : "memory");
-  if constexpr (C == 6)
-    asm volatile("s_waitcnt vmcnt(%6)"
-                 : "+v"(r[LO]), "+v"(r[LO + 1]), "+v"(r[LO + 2]), "+v"(r[LO + 3]), "+v"(r[LO + 4]), "+v"(r[LO + 5])
-                 : "n"(VM)
-                 : "memory");
-}
-
-// Registers -> LDS.
-template <int ROWS, bool KC>
-__device__ __forceinline__ void slab_store(const u32x4 (&r)[ROWS * GK / 8 / 256], char* lds) {
-#pragma unroll
-  for (int i = 0; i < TileLds<ROWS, KC>::NCHUNK; i++) {
-    const int id = threadIdx.x + i * 256;
-    if (KC) {
-      const int row = id >> 3, c = id & 7;
-      *reinterpret_cast<u32x4*>(lds + row * 128 + ((c ^ (row & 7)) << 4)) = r[i];
-    } else {
-      constexpr int CPR = ROWS / 8;
-      const int kr = id / CPR, c = id % CPR;
-      *reinterpret_cast<u32x4*>(lds + kr * TileLds<ROWS, KC>::STRIDE_MC + c * 16) = r[i];
-    }
-  }
+  constexpr int RB = ROWS * 2;  // bytes per k-row
+  const int kr = b / RB, pc = (b % RB) >> 4;
+  const int lc = (((pc >> 1) ^ (kr & 3)) << 1) | (pc & 1);
+  return P + (size_t)(k0 + kr) * ld + row0 + (lc << 3);
 }
 
 // One MFMA operand (8 bf16 per lane) for the 32 rows starting at rb, k-step ks (16 wide).
@@ -130,12 +61,12 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
     return __builtin_bit_cast(bf16x8, v);
   } else {
     const int blk = lane >> 4, i = lane & 15;
-    const int kr = ks * 16 + (blk >> 1) * 8 + (i >> 2);
+    const int kr = ks * 16 + (blk >> 1) * 8 + (i >> 2);  // kr + 4 has the same (k & 3)
     const int col = rb + (blk & 1) * 16 + (i & 3) * 4;
-    const char* p = lds + kr * TileLds<ROWS, KC>::STRIDE_MC + col * 2;
+    const char* p = lds + kr * (ROWS * 2) + (((col >> 4) ^ (kr & 3)) << 5) + (col & 15) * 2;
     typedef __attribute__((address_space(3))) short4v lds_s4;
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p + 4 * TileLds<ROWS, KC>::STRIDE_MC));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p + 4 * ROWS * 2));
     const short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
   }
@@ -260,64 +191,49 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  const int nk = K / GK;
-  {
-    u32x4 ra[LA::NCHUNK], rb[LB::NCHUNK];
-    slab_load<BM, A_KC>(ra, A, lda, m0, 0);
-    slab_load<BN, B_KC>(rb, B, ldb, n0, 0);
-    slab_store<BM, A_KC>(ra, smem);
-    slab_store<BN, B_KC>(rb, smem + LA::BYTES);
-  }
-
-  // Staging registers for the slab after next, in three groups [0,G1) [G1,G2) [G2,NS); entries
-  // below NA belong to operand A.  Group g of slab kt+1 is written to LDS in phase g of
-  // iteration kt and its registers are refilled at once with group g of slab kt+2, so every
-  // load has a full iteration of MFMAs to arrive, and LDS writes come in small bursts between
-  // the fragment reads instead of one block.  Past the last slab the final one is requested
-  // again, which keeps the outstanding-load count (and the vmcnt arguments) uniform.
-  constexpr int NA = LA::NCHUNK, NS = LA::NCHUNK + LB::NCHUNK;
-  constexpr int G1 = (NS + 2) / 3, G2 = G1 + (NS - G1 + 1) / 2;
-  constexpr int C0 = G1, C1 = G2 - G1, C2 = NS - G2;
-  u32x4 rs[NS];
-  auto issue = [&](auto lo_c, auto hi_c, int k0) {
-#pragma unroll
-    for (int i = decltype(lo_c)::value; i < decltype(hi_c)::value; i++)
-      load_issue(rs[i], i < NA ? chunk_src<BM, A_KC>(A, lda, m0, k0, i) : chunk_src<BN, B_KC>(B, ldb, n0, k0, i - NA));
+  // This wave's share of a slab: segments wave*NSEG .. +NSEG-1 of A, then of B.  Segment q of a
+  // slab is LDS bytes [1024 q, 1024 q + 1024); this lane's 16 bytes sit at +16 lane.
+  constexpr int NSA = LA::NSEG, NS = LA::NSEG + LB::NSEG;
+  auto seg_off = [&](int q) { return q < NSA ? (wave * NSA + q) * 1024 : LA::BYTES + (wave * LB::NSEG + (q - NSA)) * 1024; };
+  auto seg_src = [&](int q, int k0) {
+    return q < NSA ? slab_src<BM, A_KC>(A, lda, m0, k0, (wave * NSA + q) * 1024 + lane * 16)
+                   : slab_src<BN, B_KC>(B, ldb, n0, k0, (wave * LB::NSEG + (q - NSA)) * 1024 + lane * 16);
   };
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, G1>;
-  using I2 = std::integral_constant<int, G2>;
-  using I3 = std::integral_constant<int, NS>;
-  {
-    const int k1 = min(1, nk - 1) * GK;
-    issue(I0{}, I1{}, k1);
-    issue(I1{}, I2{}, k1);
-    issue(I2{}, I3{}, k1);
+
+  const int nk = K / GK;
+  const unsigned smem_addr = lds_addr(smem);
+#pragma unroll
+  for (int q = 0; q < NS; q++) lds_dma16(seg_src(q, 0), smem_addr + seg_off(q));
+  if (nk > 1) {
+#pragma unroll
+    for (int q = 0; q < NS; q++) lds_dma16(seg_src(q, GK), smem_addr + STAGE + seg_off(q));
   }
+  lds_dma_wait();
   __syncthreads();
 
   // Software pipeline.  A slab is four k-steps ("phases") of TM x TN MFMAs each.  Operand
   // fragments are double buffered in registers: phase s issues the LDS reads for phase s+1.
-  // One barrier per slab, between phases 2 and 3: by then every wave has read its last
-  // fragments of the current slab and written its share of the next slab to the other buffer,
-  // so phase 3 already fetches the first fragments of the next slab.
+  // One barrier per slab, between phases 2 and 3: by then every wave has read its last fragments
+  // of the current slab, so the barrier frees the current buffer; just before it each wave waits
+  // for its direct-to-LDS loads of the next slab, which were issued one slab earlier.
+  // Phase 3 then fetches the first fragments of the next slab and requests the slab after next
+  // into the buffer just freed.
   //
-  // With one wave per SIMD nothing else can fill the matrix core while this wave issues its
-  // loads and stores, so every other instruction is slotted between two MFMAs: slot t of a
-  // phase follows MFMA t and holds at most one fragment read, one LDS write and one global
-  // load.  sched_barrier after each slot keeps the compiler from regrouping them.
+  // With one wave per SIMD nothing else can fill the matrix core while this wave issues other
+  // instructions, so they are slotted between MFMAs: slot t of a phase follows MFMA t and holds
+  // at most one fragment read and one slab load.  sched_barrier after each slot keeps the
+  // compiler from regrouping them.
   static_assert(GK / 16 == 4, "pipeline below is written for four k-steps per slab");
   constexpr int NSLOT = TM * TN;
-  static_assert(TM + TN <= NSLOT && C0 <= NSLOT, "slots per phase");
+  static_assert(TM + TN <= NSLOT, "slots per phase");
   bf16x8 fa[2][TM], fb[2][TN];
-  // MFMA t of the phase running on fragment buffer `use`, then slot t: fragment read t of k-step
-  // ks from slab `src` into buffer use ^ 1 (when LOADF), and staged chunk LO + t - S0 (when in
-  // range): written to `dst`, then refilled from global k offset k2.
-  auto phase = [&](auto use_c, auto loadf_c, const char* src, int ks, auto lo_c, auto hi_c, auto vm_c, char* dst,
-                   int k2) {
-    constexpr int USE = decltype(use_c)::value, LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
-    constexpr bool LOADF = decltype(loadf_c)::value;
-    constexpr int S0 = NSLOT - (HI - LO);
+  // MFMA t of the phase running on fragment buffer USE, then slot t: fragment read t of k-step ks
+  // from slab `src` into buffer USE ^ 1 (when LOADF), and slab-load segment t (when DMA) from
+  // global k offset k_next into buffer `dst`.  No run-time branch around the loads: a branch
+  // makes the compiler wait for every outstanding load before the next LDS read.
+  auto phase = [&](auto use_c, auto loadf_c, auto dma_c, const char* src, int ks, unsigned dst, int k_next) {
+    constexpr int USE = decltype(use_c)::value;
+    constexpr bool LOADF = decltype(loadf_c)::value, DMA = decltype(dma_c)::value;
 #pragma unroll
     for (int t = 0; t < NSLOT; t++) {
       const int i = t / TN, j = t % TN;
@@ -326,13 +242,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
         if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(src, wm + t * 32, ks, lane);
         else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(src + LA::BYTES, wn + (t - TM) * 32, ks, lane);
       }
-      if (HI > LO) {
-        if (t == S0) stage_wait<LO, (HI > LO ? HI : LO + 1), decltype(vm_c)::value>(rs);
-        if (t >= S0) {
-          const int c = LO + t - S0;
-          *reinterpret_cast<u32x4*>(dst + (c < NA ? chunk_dst<BM, A_KC>(c) : LA::BYTES + chunk_dst<BN, B_KC>(c - NA))) = rs[c];
-          load_issue(rs[c], c < NA ? chunk_src<BM, A_KC>(A, lda, m0, k2, c) : chunk_src<BN, B_KC>(B, ldb, n0, k2, c - NA));
-        }
+      if (DMA) {
+#pragma unroll
+        for (int q = t; q < NS; q += NSLOT) lds_dma16(seg_src(q, k_next), dst + seg_off(q));
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -348,27 +260,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   for (int j = 0; j < TN; j++) fb[0][j] = frag_load<BN, B_KC>(smem + LA::BYTES, wn + j * 32, 0, lane);
   for (int kt = 0; kt < nk - 1; kt++) {
     const char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    const int k2 = min(kt + 2, nk - 1) * GK;
-    phase(Z{}, T_{}, cur, 1, I0{}, I1{}, std::integral_constant<int, C1 + C2>{}, nxt, k2);
-    phase(One{}, T_{}, cur, 2, I1{}, I2{}, std::integral_constant<int, C2 + C0>{}, nxt, k2);
-    phase(Z{}, T_{}, cur, 3, I2{}, I3{}, std::integral_constant<int, C0 + C1>{}, nxt, k2);
+    const char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    phase(Z{}, T_{}, F_{}, cur, 1, 0u, 0);
+    phase(One{}, T_{}, F_{}, cur, 2, 0u, 0);
+    phase(Z{}, T_{}, F_{}, cur, 3, 0u, 0);
+    lds_dma_wait();  // the next slab, requested one slab ago, is in LDS
     __syncthreads();
-    phase(One{}, T_{}, nxt, 0, Z{}, Z{}, Z{}, nxt, 0);
+    phase(One{}, T_{}, T_{}, nxt, 0, smem_addr + (kt & 1) * STAGE, min(kt + 2, nk - 1) * GK);  // past the end: the last slab again, into a dead buffer
   }
-  // Drain the re-requested last slab.  The staging registers are operands of the waits so that
-  // they stay allocated until the loads have landed: a register the compiler considers dead
-  // while a load into it is still in flight would be handed to something else and clobbered.
-  stage_wait<0, G1, 0>(rs);
-  stage_wait<G1, G2, 0>(rs);
-  stage_wait<G2, NS, 0>(rs);
   {
     const char* cur = smem + ((nk - 1) & 1) * STAGE;
-    phase(Z{}, T_{}, cur, 1, Z{}, Z{}, Z{}, nullptr, 0);
-    phase(One{}, T_{}, cur, 2, Z{}, Z{}, Z{}, nullptr, 0);
-    phase(Z{}, T_{}, cur, 3, Z{}, Z{}, Z{}, nullptr, 0);
-    phase(One{}, F_{}, cur, 0, Z{}, Z{}, Z{}, nullptr, 0);
+    phase(Z{}, T_{}, F_{}, cur, 1, 0u, 0);
+    phase(One{}, T_{}, F_{}, cur, 2, 0u, 0);
+    phase(Z{}, T_{}, F_{}, cur, 3, 0u, 0);
+    phase(One{}, F_{}, F_{}, cur, 0, 0u, 0);
   }
+  lds_dma_wait();  // the re-requested last slab: nothing may be in flight when LDS is reused or the wave ends
 
   if constexpr (EM == EM_F32) {
     // fp32 output: 32 consecutive lanes already cover 128 contiguous bytes of a row
@@ -450,7 +357,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 
 template <int BT, bool A_KC, bool B_KC, int EM>
 static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
-  constexpr size_t lds = 2 * (size_t)(TileLds<BT, A_KC>::BYTES + TileLds<BT, B_KC>::BYTES);
+  constexpr size_t lds = 2 * (size_t)(TileLds<BT, A_KC>::BYTES + TileLds<BT, B_KC>::BYTES);  // also covers the epilogue's 4 x 64 x (BT/2) floats
   auto kern = gemm_mfma_kernel<BT, BT, A_KC, B_KC, EM>;
   static bool configured = false;  // benign race: the attribute is idempotent
   if (!configured) {
