@@ -121,13 +121,14 @@ __device__ __forceinline__ void st_bf16x4(void* base, size_t idx, float4 a) {
   v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
   *reinterpret_cast<bf16x4*>((bf16_t*)base + idx) = v;
 }
+// `side` is the row's residual (R) or, for the GELU' flavours, its pre-activation (U), fetched by
+// the caller ahead of time so that its latency overlaps the LDS turn-around.
 template <int EM>
-__device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, float4 a, float4 bias) {
+__device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, float4 a, float4 bias, float4 side) {
   if (EM == EM_STORE && e.C2) st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, a);
   a.x += bias.x; a.y += bias.y; a.z += bias.z; a.w += bias.w;
-  if (e.R) {
-    const float4 r = ld_bf16x4(e.R, (size_t)m * e.ldr + n);
-    a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+  if (EM != EM_DGELU_TANH && EM != EM_DGELU_ERF && e.R) {
+    a.x += side.x; a.y += side.y; a.z += side.z; a.w += side.w;
   }
   if (EM == EM_GELU_TANH || EM == EM_GELU_ERF) {
     st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
@@ -142,7 +143,7 @@ __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, f
     return;
   }
   if (EM == EM_DGELU_TANH || EM == EM_DGELU_ERF) {
-    const float4 u = ld_bf16x4(e.U, (size_t)m * e.ldu + n);
+    const float4 u = side;
     if (EM == EM_DGELU_TANH) {
       a.x *= gelu_tanh_grad_fast(u.x); a.y *= gelu_tanh_grad_fast(u.y);
       a.z *= gelu_tanh_grad_fast(u.z); a.w *= gelu_tanh_grad_fast(u.w);
@@ -305,8 +306,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     const int ncol = n0 + wn + c4;
     float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e.bias) bias = ld_bf16x4(e.bias, ncol);
+    constexpr bool DG = EM == EM_DGELU_TANH || EM == EM_DGELU_ERF;
+    const bf16_t* sp = (const bf16_t*)(DG ? e.U : e.R);  // the one side input of this flavour, if any
+    const int lds_ = DG ? e.ldu : e.ldr;
 #pragma unroll
     for (int half = 0; half < TM / 2; half++) {
+      // request the side input of all 64 rows first: the loads fly while the tile turns through LDS
+      bf16x4 side[64 / RPI];
+      if (sp) {
+#pragma unroll
+        for (int k = 0; k < 64 / RPI; k++)
+          side[k] = *reinterpret_cast<const bf16x4*>(sp + (size_t)(m0 + wm + half * 64 + k * RPI + lane / LPR) * lds_ + ncol);
+      }
 #pragma unroll
       for (int ii = 0; ii < 2; ii++)
 #pragma unroll
@@ -317,11 +328,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll 4
+#pragma unroll
       for (int k = 0; k < 64 / RPI; k++) {
         const int row = k * RPI + lane / LPR;
         const float4 a = *reinterpret_cast<const float4*>(wbuf + row * WC + c4);
-        mfma_epilogue4<EM>(e, m0 + wm + half * 64 + row, ncol, a, bias);
+        float4 sd = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sp) sd = make_float4((float)side[k][0], (float)side[k][1], (float)side[k][2], (float)side[k][3]);
+        mfma_epilogue4<EM>(e, m0 + wm + half * 64 + row, ncol, a, bias, sd);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
