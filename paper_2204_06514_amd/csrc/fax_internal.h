@@ -183,6 +183,12 @@ __device__ __forceinline__ void lds_dma16(const void* global_src, unsigned lds_s
   const unsigned dst = __builtin_amdgcn_readfirstlane(lds_segment_addr);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(global_src) : "memory");
 }
+// Same, with the address split into a wave-uniform base (scalar registers) and a 32-bit per-lane
+// byte offset: a loop that walks the base forward then needs no vector arithmetic per load.
+__device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lane_byte_offset, unsigned lds_segment_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               : : "s"(lds_segment_addr), "v"(lane_byte_offset), "s"(uniform_base) : "memory");
+}
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- GEMM epilogue shared by the scalar and MFMA kernels ----

@@ -17,8 +17,11 @@
 // consecutive LDS bytes per wave instruction (lane i at +16 i), so both swizzles are applied on
 // the global side: each lane fetches the chunk that belongs at its LDS position.
 //
-// MFMA 32x32x16 lane layout (lane l): A/B operand = row/column (l & 31), k = 8 (l >> 5) + 0..7;
-// accumulator v = 0..15 holds C[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
+// MFMA 32x32x16 lane layout (lane l): first/second operand = row/column (l & 31) of the product,
+// k = 8 (l >> 5) + 0..7; accumulator v = 0..15 holds element [8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
+// The kernel feeds the B fragment as first operand and the A fragment as second, i.e. it
+// accumulates C^T tiles: a lane then owns row m = l & 31 of C and, in v = 4 g .. 4 g + 3, the four
+// consecutive columns n = 8 g + 4 (l >> 5) + 0..3 -- a 16-byte unit for the epilogue.
 #include <type_traits>
 
 #include "fax_internal.h"
@@ -38,18 +41,19 @@ struct TileLds {
   static constexpr int NSEG = BYTES / 1024 / 4;  // 1 KB segments (= load instructions) per wave per slab
 };
 
-// Global address of the 16 bytes that belong at LDS byte offset `b` of the slab starting at
-// (row0, k0).  Inverse of the layouts that frag_load() reads.
+// Byte offset, from the slab's first element, of the 16 bytes that belong at LDS byte offset `b`
+// of the slab.  Inverse of the layouts that frag_load() reads.  Does not depend on the slab's
+// position: each lane computes its offsets once and only the (wave-uniform) slab base moves.
 template <int ROWS, bool KC>
-__device__ __forceinline__ const bf16_t* slab_src(const bf16_t* __restrict__ P, int ld, int row0, int k0, int b) {
+__device__ __forceinline__ unsigned slab_lane_offset(int ld, int b) {
   if (KC) {
     const int row = b >> 7, pc = (b >> 4) & 7;
-    return P + (size_t)(row0 + row) * ld + k0 + ((pc ^ ((row >> 1) & 7)) << 3);
+    return (unsigned)(row * ld + ((pc ^ ((row >> 1) & 7)) << 3)) * 2u;
   }
   constexpr int RB = ROWS * 2;  // bytes per k-row
   const int kr = b / RB, pc = (b % RB) >> 4;
   const int lc = (((pc >> 1) ^ (kr & 3)) << 1) | (pc & 1);
-  return P + (size_t)(k0 + kr) * ld + row0 + (lc << 3);
+  return (unsigned)(kr * ld + (lc << 3)) * 2u;
 }
 
 // One MFMA operand (8 bf16 per lane) for the 32 rows starting at rb, k-step ks (16 wide).
@@ -73,8 +77,18 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
   }
 }
 
-// Epilogue flavours, fixed at compile time so the 16 x TM x TN stores unroll into straight code.
-enum { EM_STORE = 0, EM_GELU_TANH = 1, EM_DGELU_TANH = 2, EM_F32 = 3, EM_GELU_ERF = 4, EM_DGELU_ERF = 5 };
+// Epilogue flavours, fixed at compile time: a kind, plus flags for the optional operands.  Nothing
+// in the store loop may hang on a run-time condition: stores count towards the same counter as
+// loads on this target, so the conservative wait the compiler places where branches that contain
+// loads rejoin would also wait for every earlier store to be acknowledged, once per row.
+enum { EK_STORE = 0, EK_GELU_TANH = 1, EK_GELU_ERF = 2, EK_DGELU_TANH = 3, EK_DGELU_ERF = 4, EK_F32 = 5 };
+enum {
+  EM_RES = 8,  // bf16 kinds: add the residual R;  EK_F32: add to what C already holds
+  EM_C2 = 16   // EK_STORE: also write the plain product (before bias and residual) to C2
+};
+constexpr int em_kind(int em) { return em & 7; }
+constexpr bool em_dgelu(int em) { return em_kind(em) == EK_DGELU_TANH || em_kind(em) == EK_DGELU_ERF; }
+constexpr bool em_gelu(int em) { return em_kind(em) == EK_GELU_TANH || em_kind(em) == EK_GELU_ERF; }
 
 // tanh-form GELU through the logistic function: (1 + tanh z) / 2 = 1 / (1 + exp(-2 z)), one
 // v_exp_f32 and one v_rcp_f32 per element, a few ulp in fp32 (the outputs are rounded to bf16).
@@ -86,29 +100,6 @@ __device__ __forceinline__ float gelu_tanh_fast(float u) { return u * sigmoid2z(
 __device__ __forceinline__ float gelu_tanh_grad_fast(float u) {
   const float sg = sigmoid2z(u);
   return sg + u * sg * (1.f - sg) * 1.5957691216057308f * (1.f + 0.134145f * u * u);
-}
-
-template <int EM>
-__device__ __forceinline__ void mfma_epilogue(const EpiArgs& e, int m, int n, float acc) {
-  if (EM == EM_F32) {
-    float* c = (float*)e.C + (size_t)m * e.ldc + n;
-    *c = e.accumulate ? *c + acc : acc;
-    return;
-  }
-  if (EM == EM_STORE && e.C2) ((bf16_t*)e.C2)[(size_t)m * e.ldc2 + n] = (bf16_t)acc;
-  if (e.bias) acc += (float)((const bf16_t*)e.bias)[n];
-  if (e.R) acc += (float)((const bf16_t*)e.R)[(size_t)m * e.ldr + n];
-  if (EM == EM_GELU_TANH || EM == EM_GELU_ERF) {
-    ((bf16_t*)e.C)[(size_t)m * e.ldc + n] = (bf16_t)acc;
-    const float a = EM == EM_GELU_TANH ? gelu_tanh_fast(acc) : gelu_f(acc, FAX_GELU_ERF);
-    ((bf16_t*)e.C2)[(size_t)m * e.ldc2 + n] = (bf16_t)a;
-    return;
-  }
-  if (EM == EM_DGELU_TANH || EM == EM_DGELU_ERF) {
-    const float u = (float)((const bf16_t*)e.U)[(size_t)m * e.ldu + n];
-    acc *= EM == EM_DGELU_TANH ? gelu_tanh_grad_fast(u) : gelu_grad_f(u, FAX_GELU_ERF);
-  }
-  ((bf16_t*)e.C)[(size_t)m * e.ldc + n] = (bf16_t)acc;
 }
 
 // Four consecutive columns n..n+3 of row m at once: 8-byte bf16 loads and stores.
@@ -124,17 +115,24 @@ __device__ __forceinline__ void st_bf16x4(void* base, size_t idx, float4 a) {
 }
 // `side` is the row's residual (R) or, for the GELU' flavours, its pre-activation (U), fetched by
 // the caller ahead of time so that its latency overlaps the LDS turn-around.
+// For the fp32 flavour (plain product, optionally added to what C holds) `side` is the old C.
 template <int EM>
 __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, float4 a, float4 bias, float4 side) {
-  if (EM == EM_STORE && e.C2) st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, a);
+  constexpr int KIND = em_kind(EM);
+  if (KIND == EK_F32) {
+    if (EM & EM_RES) { a.x += side.x; a.y += side.y; a.z += side.z; a.w += side.w; }
+    *reinterpret_cast<float4*>((float*)e.C + (size_t)m * e.ldc + n) = a;
+    return;
+  }
+  if (EM & EM_C2) st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, a);
   a.x += bias.x; a.y += bias.y; a.z += bias.z; a.w += bias.w;
-  if (EM != EM_DGELU_TANH && EM != EM_DGELU_ERF && e.R) {
+  if (!em_dgelu(EM) && (EM & EM_RES)) {
     a.x += side.x; a.y += side.y; a.z += side.z; a.w += side.w;
   }
-  if (EM == EM_GELU_TANH || EM == EM_GELU_ERF) {
+  if (em_gelu(EM)) {
     st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
     float4 g;
-    if (EM == EM_GELU_TANH) {
+    if (KIND == EK_GELU_TANH) {
       g = make_float4(gelu_tanh_fast(a.x), gelu_tanh_fast(a.y), gelu_tanh_fast(a.z), gelu_tanh_fast(a.w));
     } else {
       g = make_float4(gelu_f(a.x, FAX_GELU_ERF), gelu_f(a.y, FAX_GELU_ERF), gelu_f(a.z, FAX_GELU_ERF),
@@ -143,9 +141,9 @@ __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, f
     st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, g);
     return;
   }
-  if (EM == EM_DGELU_TANH || EM == EM_DGELU_ERF) {
+  if (em_dgelu(EM)) {
     const float4 u = side;
-    if (EM == EM_DGELU_TANH) {
+    if (KIND == EK_DGELU_TANH) {
       a.x *= gelu_tanh_grad_fast(u.x); a.y *= gelu_tanh_grad_fast(u.y);
       a.z *= gelu_tanh_grad_fast(u.z); a.w *= gelu_tanh_grad_fast(u.w);
     } else {
@@ -182,7 +180,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   const int tn_i = (id % per_group) / gsz;
   const int m0 = tm_i * BM, n0 = tn_i * BN;
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // in a scalar register: LDS segment addresses stay scalar
   const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
 
   f32x16 acc[TM][TN];
@@ -194,21 +193,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   // This wave's share of a slab: segments wave*NSEG .. +NSEG-1 of A, then of B.  Segment q of a
-  // slab is LDS bytes [1024 q, 1024 q + 1024); this lane's 16 bytes sit at +16 lane.
+  // slab is LDS bytes [1024 q, 1024 q + 1024); this lane's 16 bytes sit at +16 lane.  The global
+  // address of a segment is (uniform slab base) + (this lane's offset, fixed for the whole
+  // kernel), so stepping along K is scalar arithmetic only.
   constexpr int NSA = LA::NSEG, NS = LA::NSEG + LB::NSEG;
   auto seg_off = [&](int q) { return q < NSA ? (wave * NSA + q) * 1024 : LA::BYTES + (wave * LB::NSEG + (q - NSA)) * 1024; };
-  auto seg_src = [&](int q, int k0) {
-    return q < NSA ? slab_src<BM, A_KC>(A, lda, m0, k0, (wave * NSA + q) * 1024 + lane * 16)
-                   : slab_src<BN, B_KC>(B, ldb, n0, k0, (wave * LB::NSEG + (q - NSA)) * 1024 + lane * 16);
+  unsigned lane_off[NS];
+#pragma unroll
+  for (int q = 0; q < NS; q++)
+    lane_off[q] = q < NSA ? slab_lane_offset<BM, A_KC>(lda, (wave * NSA + q) * 1024 + lane * 16)
+                          : slab_lane_offset<BN, B_KC>(ldb, (wave * LB::NSEG + (q - NSA)) * 1024 + lane * 16);
+  const bf16_t* const a_tile = A + (A_KC ? (size_t)m0 * lda : (size_t)m0);
+  const bf16_t* const b_tile = B + (B_KC ? (size_t)n0 * ldb : (size_t)n0);
+  const size_t a_kstride = A_KC ? 1 : (size_t)lda, b_kstride = B_KC ? 1 : (size_t)ldb;
+  auto slab_dma = [&](int q, int k0, unsigned dst) {
+    lds_dma16(q < NSA ? a_tile + k0 * a_kstride : b_tile + k0 * b_kstride, lane_off[q], dst + seg_off(q));
   };
 
   const int nk = K / GK;
   const unsigned smem_addr = lds_addr(smem);
 #pragma unroll
-  for (int q = 0; q < NS; q++) lds_dma16(seg_src(q, 0), smem_addr + seg_off(q));
+  for (int q = 0; q < NS; q++) slab_dma(q, 0, smem_addr);
   if (nk > 1) {
 #pragma unroll
-    for (int q = 0; q < NS; q++) lds_dma16(seg_src(q, GK), smem_addr + STAGE + seg_off(q));
+    for (int q = 0; q < NS; q++) slab_dma(q, GK, smem_addr + STAGE);
   }
   lds_dma_wait();
   __syncthreads();
@@ -239,14 +247,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 #pragma unroll
     for (int t = 0; t < NSLOT; t++) {
       const int i = t / TN, j = t % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[USE][i], fb[USE][j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[USE][j], fa[USE][i], acc[i][j], 0, 0, 0);  // C^T tile
       if (LOADF) {
         if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(src, wm + t * 32, ks, lane);
         else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(src + LA::BYTES, wn + (t - TM) * 32, ks, lane);
       }
       if (DMA) {
 #pragma unroll
-        for (int q = t; q < NS; q += NSLOT) lds_dma16(seg_src(q, k_next), dst + seg_off(q));
+        for (int q = t; q < NS; q += NSLOT) slab_dma(q, k_next, dst);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -279,68 +287,80 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   }
   lds_dma_wait();  // the re-requested last slab: nothing may be in flight when LDS is reused or the wave ends
 
-  if constexpr (EM == EM_F32) {
-    // fp32 output: 32 consecutive lanes already cover 128 contiguous bytes of a row
+  // Epilogue.  Each wave turns 64 rows of its tile at a time through its own quarter of LDS
+  // (fp32) and reads them back row-wise, four consecutive columns per lane, so that a row of the
+  // wave tile leaves as one contiguous run and bias, residual and the GELU side inputs move as
+  // 8-byte vectors.  On the way in a lane writes the 16-byte units it owns (row l & 31); the
+  // 16-byte chunk index is XOR-ed with (row & 7) so that neither those writes (8 lanes = 8 rows,
+  // same chunk) nor the row-wise reads (8 lanes = 8 consecutive chunks) collide on LDS banks.
+  // Reads are issued eight rows ahead of the arithmetic and stores that consume them.
+  constexpr int WC = TN * 32;     // columns of the wave tile
+  constexpr int LPR = WC / 4;     // lanes per row on the way out
+  constexpr int RPI = 64 / LPR;   // rows per store instruction
+  constexpr int NIT = 64 / RPI;   // store instructions per 64 rows
+  constexpr int BATCH = 8;
+  static_assert(NIT % BATCH == 0, "batching of the read-back");
+  __syncthreads();                // every wave is done with the operand slabs
+  float* wbuf = reinterpret_cast<float*>(smem) + wave * 64 * WC;
+  const int c4 = (lane % LPR) * 4;
+  const int rsub = lane / LPR;
+  const int ncol = n0 + wn + c4;
+  constexpr bool F32 = em_kind(EM) == EK_F32, DG = em_dgelu(EM);
+  constexpr bool SIDE = !F32 && (DG || (EM & EM_RES));  // a bf16 side input: pre-activation U or residual R
+  float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (!F32 && e.bias) bias = ld_bf16x4(e.bias, ncol);
+  const bf16_t* sp = (const bf16_t*)(DG ? e.U : e.R);
+  const int lds_ = DG ? e.ldu : e.ldr;
 #pragma unroll
-    for (int i = 0; i < TM; i++)
+  for (int half = 0; half < TM / 2; half++) {
+    const int mrow = m0 + wm + half * 64 + rsub;
+    // request the side input of all 64 rows first: the loads fly while the tile turns through LDS
+    bf16x4 side[SIDE ? NIT : 1];
+    if (SIDE) {
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        const int n = n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const int m = m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          mfma_epilogue<EM>(e, m, n, acc[i][j][v]);
-        }
-      }
-  } else {
-    // bf16 outputs: an accumulator register holds one column of four different rows, which would
-    // mean 2-byte stores scattered over rows.  Each wave instead turns 64 rows of its tile at a
-    // time through its own quarter of LDS (fp32) and reads them back row-wise, four consecutive
-    // columns per lane, so bias, residual and the GELU side inputs move as 8-byte vectors and a
-    // row of the wave tile leaves as one contiguous run.
-    constexpr int WC = TN * 32;   // columns of the wave tile
-    constexpr int LPR = WC / 4;   // lanes per row on the way out
-    constexpr int RPI = 64 / LPR; // rows per store instruction
-    __syncthreads();              // every wave is done with the operand slabs
-    float* wbuf = reinterpret_cast<float*>(smem) + wave * 64 * WC;
-    const int c4 = (lane % LPR) * 4;
-    const int ncol = n0 + wn + c4;
-    float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (e.bias) bias = ld_bf16x4(e.bias, ncol);
-    constexpr bool DG = EM == EM_DGELU_TANH || EM == EM_DGELU_ERF;
-    const bf16_t* sp = (const bf16_t*)(DG ? e.U : e.R);  // the one side input of this flavour, if any
-    const int lds_ = DG ? e.ldu : e.ldr;
-#pragma unroll
-    for (int half = 0; half < TM / 2; half++) {
-      // request the side input of all 64 rows first: the loads fly while the tile turns through LDS
-      bf16x4 side[64 / RPI];
-      if (sp) {
-#pragma unroll
-        for (int k = 0; k < 64 / RPI; k++)
-          side[k] = *reinterpret_cast<const bf16x4*>(sp + (size_t)(m0 + wm + half * 64 + k * RPI + lane / LPR) * lds_ + ncol);
-      }
-#pragma unroll
-      for (int ii = 0; ii < 2; ii++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-#pragma unroll
-          for (int v = 0; v < 16; v++)
-            wbuf[(ii * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * WC + j * 32 + (lane & 31)] = acc[half * 2 + ii][j][v];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-      for (int k = 0; k < 64 / RPI; k++) {
-        const int row = k * RPI + lane / LPR;
-        const float4 a = *reinterpret_cast<const float4*>(wbuf + row * WC + c4);
-        float4 sd = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (sp) sd = make_float4((float)side[k][0], (float)side[k][1], (float)side[k][2], (float)side[k][3]);
-        mfma_epilogue4<EM>(e, m0 + wm + half * 64 + row, ncol, a, bias, sd);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      for (int k = 0; k < NIT; k++)
+        side[k] = *reinterpret_cast<const bf16x4*>(sp + (size_t)(mrow + k * RPI) * lds_ + ncol);
     }
+#pragma unroll
+    for (int ii = 0; ii < 2; ii++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          const int row = ii * 32 + (lane & 31);
+          const int chunk = j * 8 + g * 2 + (lane >> 5);
+          const f32x16& t = acc[half * 2 + ii][j];
+          *reinterpret_cast<float4*>(wbuf + row * WC + ((chunk ^ (row & 7)) << 2)) =
+              make_float4(t[g * 4], t[g * 4 + 1], t[g * 4 + 2], t[g * 4 + 3]);
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k0 = 0; k0 < NIT; k0 += BATCH) {
+      constexpr bool ADD_C = F32 && (EM & EM_RES);
+      float4 a[BATCH], old_c[ADD_C ? BATCH : 1];
+#pragma unroll
+      for (int u = 0; u < BATCH; u++) {
+        const int row = (k0 + u) * RPI + rsub;
+        a[u] = *reinterpret_cast<const float4*>(wbuf + row * WC + (((c4 >> 2) ^ (row & 7)) << 2));
+        if (ADD_C) old_c[u] = *reinterpret_cast<const float4*>((const float*)e.C + (size_t)(mrow + (k0 + u) * RPI) * e.ldc + ncol);
+      }
+#pragma unroll
+      for (int u = 0; u < BATCH; u++) {
+        float4 sd = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ADD_C) {
+          sd = old_c[u];
+        } else if (SIDE) {
+          const bf16x4 v = side[k0 + u];
+          sd = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+        }
+        mfma_epilogue4<EM>(e, mrow + (k0 + u) * RPI, ncol, a[u], bias, sd);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 }
 
@@ -357,11 +377,15 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.c_f32 && (g.bias || g.R || g.C2 || g.epi != EPI_NONE)) return false;  // fp32 C is the plain weight-gradient form
   // the GELU epilogues exist for the orientations the block uses them in: forward (A [M,K], B [K,N])
   // and input-gradient (A [M,K], B [N,K])
-  if (g.epi == EPI_GELU && (g.ta || g.tb)) return false;
-  if (g.epi == EPI_DGELU && (g.ta || !g.tb)) return false;
+  if (g.epi == EPI_GELU && (g.ta || g.tb || g.R)) return false;
+  if (g.epi == EPI_DGELU && (g.ta || !g.tb || g.R)) return false;
+  // the second output likewise: forward orientation only
+  if (g.epi == EPI_NONE && g.C2 && (g.ta || g.tb)) return false;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % GK != 0) return false;
   if (g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return false;
-  if (!g.c_f32) {  // the bf16 epilogue moves four columns at a time
+  if (g.c_f32) {  // the epilogue moves four columns at a time: 16-byte fp32 units ...
+    if (g.ldc % 4 || !aligned16(g.C)) return false;
+  } else {        // ... or 8-byte bf16 units
     auto vec_ok = [](const void* p, int ld) { return !p || (ld % 4 == 0 && (reinterpret_cast<uintptr_t>(p) & 7) == 0); };
     if (!vec_ok(g.C, g.ldc) || !vec_ok(g.C2, g.ldc2) || !vec_ok(g.R, g.ldr) || !vec_ok(g.U, g.ldu) || !vec_ok(g.bias, 4))
       return false;
@@ -390,19 +414,34 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   const bool a_kc = !g.ta, b_kc = g.tb;
   const bool erf = g.gelu_form == FAX_GELU_ERF;
   if (g.epi == EPI_GELU)
-    return erf ? launch_mfma<BT, true, false, EM_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EM_GELU_TANH>(g, e, s);
+    return erf ? launch_mfma<BT, true, false, EK_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EK_GELU_TANH>(g, e, s);
   if (g.epi == EPI_DGELU)
-    return erf ? launch_mfma<BT, true, true, EM_DGELU_ERF>(g, e, s) : launch_mfma<BT, true, true, EM_DGELU_TANH>(g, e, s);
+    return erf ? launch_mfma<BT, true, true, EK_DGELU_ERF>(g, e, s) : launch_mfma<BT, true, true, EK_DGELU_TANH>(g, e, s);
   if (g.c_f32) {
-    if (a_kc && b_kc) return launch_mfma<BT, true, true, EM_F32>(g, e, s);
-    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EM_F32>(g, e, s);
-    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EM_F32>(g, e, s);
-    return launch_mfma<BT, false, false, EM_F32>(g, e, s);
+    if (g.accumulate) {
+      if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_F32 | EM_RES>(g, e, s);
+      if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_F32 | EM_RES>(g, e, s);
+      if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_F32 | EM_RES>(g, e, s);
+      return launch_mfma<BT, false, false, EK_F32 | EM_RES>(g, e, s);
+    }
+    if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_F32>(g, e, s);
+    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_F32>(g, e, s);
+    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_F32>(g, e, s);
+    return launch_mfma<BT, false, false, EK_F32>(g, e, s);
   }
-  if (a_kc && b_kc) return launch_mfma<BT, true, true, EM_STORE>(g, e, s);
-  if (a_kc && !b_kc) return launch_mfma<BT, true, false, EM_STORE>(g, e, s);
-  if (!a_kc && b_kc) return launch_mfma<BT, false, true, EM_STORE>(g, e, s);
-  return launch_mfma<BT, false, false, EM_STORE>(g, e, s);
+  if (g.C2)  // forward orientation (checked by gemm_mfma_supported)
+    return g.R ? launch_mfma<BT, true, false, EK_STORE | EM_RES | EM_C2>(g, e, s)
+               : launch_mfma<BT, true, false, EK_STORE | EM_C2>(g, e, s);
+  if (g.R) {
+    if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_STORE | EM_RES>(g, e, s);
+    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_STORE | EM_RES>(g, e, s);
+    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_STORE | EM_RES>(g, e, s);
+    return launch_mfma<BT, false, false, EK_STORE | EM_RES>(g, e, s);
+  }
+  if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_STORE>(g, e, s);
+  if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_STORE>(g, e, s);
+  if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_STORE>(g, e, s);
+  return launch_mfma<BT, false, false, EK_STORE>(g, e, s);
 }
 
 int gemm_mfma(const GemmArgs& g, hipStream_t s) {
