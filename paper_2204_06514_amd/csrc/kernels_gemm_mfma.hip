@@ -2,8 +2,9 @@
 //
 // One 256-thread workgroup (4 wavefronts, 2x2) computes a BM x BN tile of C, stepping over K in
 // slabs of 64.  Slabs of A and B go from global memory straight into LDS
-// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), double buffered,
-// each requested a full slab of MFMAs before it is needed.
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), three buffers for
+// A and two for B, each slab requested about a slab of MFMAs before it is needed and its load
+// instructions spread over that time.
 //
 // An operand whose contraction index is contiguous in memory ("KC": A stored [M,K], B stored
 // [N,K]) is kept in LDS as [row][64] with the 16-byte chunk index XOR-ed with ((row >> 1) & 7):
@@ -32,6 +33,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+template <int V> using I = std::integral_constant<int, V>;
+using T_ = std::true_type;
+using F_ = std::false_type;
 
 static constexpr int GK = 64;  // K slab
 
@@ -162,7 +166,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   using LB = TileLds<BN, B_KC>;
   constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA tiles per wave in each direction
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int STAGE = LA::BYTES + LB::BYTES;  // [A slab | B slab] per buffer, two buffers
+  // LDS: three buffers for A slabs, then two for B slabs (see the pipeline below).
+  constexpr int A_BUFS = 3, B_BUFS = 2;
+  constexpr int B_BASE = A_BUFS * LA::BYTES;
 
   // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with
   // its own L2), so id is first re-dealt so that each XCD owns a contiguous run of tiles, then
@@ -192,98 +198,132 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  // This wave's share of a slab: segments wave*NSEG .. +NSEG-1 of A, then of B.  Segment q of a
-  // slab is LDS bytes [1024 q, 1024 q + 1024); this lane's 16 bytes sit at +16 lane.  The global
-  // address of a segment is (uniform slab base) + (this lane's offset, fixed for the whole
-  // kernel), so stepping along K is scalar arithmetic only.
-  constexpr int NSA = LA::NSEG, NS = LA::NSEG + LB::NSEG;
-  auto seg_off = [&](int q) { return q < NSA ? (wave * NSA + q) * 1024 : LA::BYTES + (wave * LB::NSEG + (q - NSA)) * 1024; };
-  unsigned lane_off[NS];
+  // This wave's share of a slab: segments wave*NSEG .. +NSEG-1 of A and likewise of B.  Segment
+  // q of a slab is bytes [1024 q, 1024 q + 1024) of its buffer; this lane's 16 bytes sit at
+  // +16 lane.  The global address of a segment is (uniform slab base) + (this lane's offset,
+  // fixed for the whole kernel), so stepping along K is scalar arithmetic only.
+  constexpr int NSA = LA::NSEG, NSB = LB::NSEG;
+  unsigned a_lane_off[NSA], b_lane_off[NSB];
 #pragma unroll
-  for (int q = 0; q < NS; q++)
-    lane_off[q] = q < NSA ? slab_lane_offset<BM, A_KC>(lda, (wave * NSA + q) * 1024 + lane * 16)
-                          : slab_lane_offset<BN, B_KC>(ldb, (wave * LB::NSEG + (q - NSA)) * 1024 + lane * 16);
+  for (int q = 0; q < NSA; q++) a_lane_off[q] = slab_lane_offset<BM, A_KC>(lda, (wave * NSA + q) * 1024 + lane * 16);
+#pragma unroll
+  for (int q = 0; q < NSB; q++) b_lane_off[q] = slab_lane_offset<BN, B_KC>(ldb, (wave * NSB + q) * 1024 + lane * 16);
   const bf16_t* const a_tile = A + (A_KC ? (size_t)m0 * lda : (size_t)m0);
   const bf16_t* const b_tile = B + (B_KC ? (size_t)n0 * ldb : (size_t)n0);
   const size_t a_kstride = A_KC ? 1 : (size_t)lda, b_kstride = B_KC ? 1 : (size_t)ldb;
-  auto slab_dma = [&](int q, int k0, unsigned dst) {
-    lds_dma16(q < NSA ? a_tile + k0 * a_kstride : b_tile + k0 * b_kstride, lane_off[q], dst + seg_off(q));
+  const unsigned smem_addr = lds_addr(smem);
+  // segment q of the A (B) slab at k0 -> A (B) buffer number `buf`
+  auto dma_a = [&](int q, int k0, int buf) {
+    lds_dma16(a_tile + k0 * a_kstride, a_lane_off[q], smem_addr + buf * LA::BYTES + (wave * NSA + q) * 1024);
+  };
+  auto dma_b = [&](int q, int k0, int buf) {
+    lds_dma16(b_tile + k0 * b_kstride, b_lane_off[q], smem_addr + B_BASE + buf * LB::BYTES + (wave * NSB + q) * 1024);
   };
 
   const int nk = K / GK;
-  const unsigned smem_addr = lds_addr(smem);
 #pragma unroll
-  for (int q = 0; q < NS; q++) slab_dma(q, 0, smem_addr);
+  for (int q = 0; q < NSA; q++) dma_a(q, 0, 0);
+#pragma unroll
+  for (int q = 0; q < NSB; q++) dma_b(q, 0, 0);
   if (nk > 1) {
 #pragma unroll
-    for (int q = 0; q < NS; q++) slab_dma(q, GK, smem_addr + STAGE);
+    for (int q = 0; q < NSA; q++) dma_a(q, GK, 1);
+#pragma unroll
+    for (int q = 0; q < NSB; q++) dma_b(q, GK, 1);
   }
   lds_dma_wait();
   __syncthreads();
 
   // Software pipeline.  A slab is four k-steps ("phases") of TM x TN MFMAs each.  Operand
   // fragments are double buffered in registers: phase s issues the LDS reads for phase s+1.
-  // One barrier per slab, between phases 2 and 3: by then every wave has read its last fragments
-  // of the current slab, so the barrier frees the current buffer; just before it each wave waits
-  // for its direct-to-LDS loads of the next slab, which were issued one slab earlier.
-  // Phase 3 then fetches the first fragments of the next slab and requests the slab after next
-  // into the buffer just freed.
   //
   // With one wave per SIMD nothing else can fill the matrix core while this wave issues other
   // instructions, so they are slotted between MFMAs: slot t of a phase follows MFMA t and holds
   // at most one fragment read and one slab load.  sched_barrier after each slot keeps the
   // compiler from regrouping them.
+  //
+  // The slab loads set the pace of the schedule.  The CU's address unit takes 16 cycles per
+  // 1 KB load instruction and is shared by the four waves, so a slab (64 instructions at 256^2)
+  // keeps it busy for half of the slab's MFMA time: requested in one burst, the loads block the
+  // issuing waves and with them the matrix cores.  They are therefore spread over the whole slab,
+  // which needs somewhere to put them while both resident slabs are still being read: A gets a
+  // third buffer.  While slab kt is multiplied,
+  //   phases 0-1:          request A(kt+2) into the spare A buffer, a load every few slots;
+  //   phase 2, slot PB:    all fragment reads of slab kt are done; wait until everything older
+  //                        than the A loads just issued has landed (that is slab kt+1), barrier:
+  //                        slab kt+1 is published and the B buffer of slab kt is free;
+  //   rest of phase 2, 3:  request B(kt+2) into that buffer; phase 3 also reads the first
+  //                        fragments of slab kt+1.
+  // One barrier per slab.  PB leaves four MFMAs between the last fragment read and the wait.
   static_assert(GK / 16 == 4, "pipeline below is written for four k-steps per slab");
   constexpr int NSLOT = TM * TN;
   static_assert(TM + TN <= NSLOT, "slots per phase");
+  constexpr int PB = (TM + TN + 4 < NSLOT) ? TM + TN + 4 : NSLOT;  // barrier position within phase 2
+  constexpr int SLOTS_A = 2 * NSLOT;             // slots open to the A loads
+  constexpr int SLOTS_B = NSLOT - PB + NSLOT;    // ... and to the B loads
+  static_assert(NSA <= SLOTS_A && NSB <= SLOTS_B && NSA < 64, "load schedule");
   bf16x8 fa[2][TM], fb[2][TN];
-  // MFMA t of the phase running on fragment buffer USE, then slot t: fragment read t of k-step ks
-  // from slab `src` into buffer USE ^ 1 (when LOADF), and slab-load segment t (when DMA) from
-  // global k offset k_next into buffer `dst`.  No run-time branch around the loads: a branch
-  // makes the compiler wait for every outstanding load before the next LDS read.
-  auto phase = [&](auto use_c, auto loadf_c, auto dma_c, const char* src, int ks, unsigned dst, int k_next) {
-    constexpr int USE = decltype(use_c)::value;
-    constexpr bool LOADF = decltype(loadf_c)::value, DMA = decltype(dma_c)::value;
+  // Slots [T0, T1) of one phase: MFMA t on fragment buffer USE, then fragment read t of k-step ks
+  // from (srcA, srcB) into buffer USE ^ 1 (when LOADF), then the slab loads that the schedule
+  // puts at this slot: LOADS 1 = A loads, slot number t + OFS of SLOTS_A; LOADS 2 = B loads,
+  // slot number t + OFS of SLOTS_B; segment q goes to slot floor(q * SLOTS / NSEG).
+  auto phase = [&](auto use_c, auto loadf_c, auto loads_c, auto ofs_c, auto t0_c, auto t1_c, const char* srcA,
+                   const char* srcB, int ks, int k_next, int buf) {
+    constexpr int USE = decltype(use_c)::value, LOADS = decltype(loads_c)::value, OFS = decltype(ofs_c)::value;
+    constexpr int T0 = decltype(t0_c)::value, T1 = decltype(t1_c)::value;
+    constexpr bool LOADF = decltype(loadf_c)::value;
 #pragma unroll
-    for (int t = 0; t < NSLOT; t++) {
+    for (int t = T0; t < T1; t++) {
       const int i = t / TN, j = t % TN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[USE][j], fa[USE][i], acc[i][j], 0, 0, 0);  // C^T tile
       if (LOADF) {
-        if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(src, wm + t * 32, ks, lane);
-        else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(src + LA::BYTES, wn + (t - TM) * 32, ks, lane);
+        if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(srcA, wm + t * 32, ks, lane);
+        else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(srcB, wn + (t - TM) * 32, ks, lane);
       }
-      if (DMA) {
+      if (LOADS == 1) {
 #pragma unroll
-        for (int q = t; q < NS; q += NSLOT) slab_dma(q, k_next, dst);
+        for (int q = 0; q < NSA; q++)
+          if (q * SLOTS_A / NSA == t + OFS) dma_a(q, k_next, buf);
+      }
+      if (LOADS == 2) {
+#pragma unroll
+        for (int q = 0; q < NSB; q++)
+          if (q * SLOTS_B / NSB == t + OFS) dma_b(q, k_next, buf);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  using Z = std::integral_constant<int, 0>;
-  using One = std::integral_constant<int, 1>;
-  using T_ = std::true_type;
-  using F_ = std::false_type;
+  auto a_buf = [&](int i) { return smem + i * LA::BYTES; };
+  auto b_buf = [&](int i) { return smem + B_BASE + i * LB::BYTES; };
 
 #pragma unroll
-  for (int i = 0; i < TM; i++) fa[0][i] = frag_load<BM, A_KC>(smem, wm + i * 32, 0, lane);
+  for (int i = 0; i < TM; i++) fa[0][i] = frag_load<BM, A_KC>(a_buf(0), wm + i * 32, 0, lane);
 #pragma unroll
-  for (int j = 0; j < TN; j++) fb[0][j] = frag_load<BN, B_KC>(smem + LA::BYTES, wn + j * 32, 0, lane);
+  for (int j = 0; j < TN; j++) fb[0][j] = frag_load<BN, B_KC>(b_buf(0), wn + j * 32, 0, lane);
+  int ia = 0;  // A buffer of the current slab: kt mod 3
   for (int kt = 0; kt < nk - 1; kt++) {
-    const char* cur = smem + (kt & 1) * STAGE;
-    const char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    phase(Z{}, T_{}, F_{}, cur, 1, 0u, 0);
-    phase(One{}, T_{}, F_{}, cur, 2, 0u, 0);
-    phase(Z{}, T_{}, F_{}, cur, 3, 0u, 0);
-    lds_dma_wait();  // the next slab, requested one slab ago, is in LDS
-    __syncthreads();
-    phase(One{}, T_{}, T_{}, nxt, 0, smem_addr + (kt & 1) * STAGE, min(kt + 2, nk - 1) * GK);  // past the end: the last slab again, into a dead buffer
+    const int ia1 = ia == 2 ? 0 : ia + 1, ia2 = ia1 == 2 ? 0 : ia1 + 1;
+    const int ib = kt & 1;
+    const char* curA = a_buf(ia);
+    const char* curB = b_buf(ib);
+    const int k_next = min(kt + 2, nk - 1) * GK;  // past the end: the last slab again, into buffers nobody reads
+    phase(I<0>{}, T_{}, I<1>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 1, k_next, ia2);
+    phase(I<1>{}, T_{}, I<1>{}, I<NSLOT>{}, I<0>{}, I<NSLOT>{}, curA, curB, 2, k_next, ia2);
+    phase(I<0>{}, T_{}, I<0>{}, I<0>{}, I<0>{}, I<PB>{}, curA, curB, 3, 0, 0);
+    // Every fragment read of slab kt has returned (lgkmcnt) and, of this wave's loads, only the
+    // NSA newest (A of slab kt+2) may still be in flight: slab kt+1 has landed.
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(NSA) : "memory");
+    phase(I<0>{}, F_{}, I<2>{}, I<-PB>{}, I<PB>{}, I<NSLOT>{}, curA, curB, 3, k_next, ib);
+    phase(I<1>{}, T_{}, I<2>{}, I<NSLOT - PB>{}, I<0>{}, I<NSLOT>{}, a_buf(ia1), b_buf(ib ^ 1), 0, k_next, ib);
+    ia = ia1;
   }
   {
-    const char* cur = smem + ((nk - 1) & 1) * STAGE;
-    phase(Z{}, T_{}, F_{}, cur, 1, 0u, 0);
-    phase(One{}, T_{}, F_{}, cur, 2, 0u, 0);
-    phase(Z{}, T_{}, F_{}, cur, 3, 0u, 0);
-    phase(One{}, F_{}, F_{}, cur, 0, 0u, 0);
+    const char* curA = a_buf(ia);
+    const char* curB = b_buf((nk - 1) & 1);
+    phase(I<0>{}, T_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 1, 0, 0);
+    phase(I<1>{}, T_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 2, 0, 0);
+    phase(I<0>{}, T_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 3, 0, 0);
+    phase(I<1>{}, F_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 0, 0, 0);
   }
   lds_dma_wait();  // the re-requested last slab: nothing may be in flight when LDS is reused or the wave ends
 
@@ -395,7 +435,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 
 template <int BT, bool A_KC, bool B_KC, int EM>
 static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
-  constexpr size_t lds = 2 * (size_t)(TileLds<BT, A_KC>::BYTES + TileLds<BT, B_KC>::BYTES);  // also covers the epilogue's 4 x 64 x (BT/2) floats
+  constexpr size_t lds = 3 * (size_t)TileLds<BT, A_KC>::BYTES + 2 * (size_t)TileLds<BT, B_KC>::BYTES;  // 160 KB at 256^2; also covers the epilogue's 4 x 64 x (BT/2) floats
   auto kern = gemm_mfma_kernel<BT, BT, A_KC, B_KC, EM>;
   static bool configured = false;  // benign race: the attribute is idempotent
   if (!configured) {
