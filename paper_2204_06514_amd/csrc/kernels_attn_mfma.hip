@@ -24,6 +24,8 @@
 //
 // No atomics: dQ has one writer per query row, dK/dV one writer per key row; S and dP are
 // recomputed in both backward kernels (7 tile products instead of 5).
+#include <type_traits>
+
 #include "fax_internal.h"
 
 namespace fax {
@@ -33,6 +35,8 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+using T_ = std::true_type;
+using F_ = std::false_type;
 
 static constexpr float LOG2E = 1.4426950408889634f;
 static constexpr int TR = 64;  // rows per LDS tile
@@ -96,6 +100,14 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int h) {
 
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
+// The tiles arrive through inline-assembly loads that the compiler does not count.  A value it
+// loads itself before the main loop and first uses inside it makes the compiler put its own
+// "at most N loads outstanding" wait inside the loop, which then also waits for the tile loads
+// issued a moment earlier, every iteration.  Passing such values through here forces that wait to
+// happen once, before the loop.
+template <typename T>
+__device__ __forceinline__ void settle(T& v) { asm volatile("" : "+v"(v)); }
+
 // Store a transposed 32(d) x 32(row) accumulator set: lane owns one row, DH/32 tiles of 16 d's.
 template <int DH>
 __device__ __forceinline__ void store_rows(bf16_t* __restrict__ dst, const f32x16 (&acc)[DH / 32], float mul, int g) {
@@ -110,229 +122,334 @@ __device__ __forceinline__ void store_rows(bf16_t* __restrict__ dst, const f32x1
     }
 }
 
+template <int DH>
+__device__ __forceinline__ void tile_dma_seg(unsigned lds, const bf16_t* __restrict__ src, size_t ld, int i) {
+  constexpr int NCH = DH / 8, RPI = 64 / NCH;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int seg = wave * (DH / 32) + i;
+  const int row = seg * RPI + lane / NCH;
+  const int chunk = (lane % NCH) ^ swz(row);
+  lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
+}
+
+// Workgroup -> (pair of 128-row tiles, batch-head) for the three kernels.  Under the causal mask
+// row tile r of the forward / dQ kernels meets r + 1 key blocks and key tile r of the dK/dV
+// kernel meets n - r query blocks, so tiles p and n - 1 - p are done by one workgroup, one after
+// the other: every workgroup then has the same amount of work and the grid drains without a
+// ragged tail.  Consecutive workgroup ids go to different XCDs; all workgroups of one
+// (batch, head) are dealt to the same XCD so that its K/V (Q/dO) stay in that XCD's L2.
+__device__ __forceinline__ void pair_of_tiles(int n_tiles, int BH, int& pair, int& bh) {
+  const int n_pair = (n_tiles + 1) / 2;
+  if (BH % 8 == 0) {
+    const int slot = blockIdx.x / 8;
+    bh = (slot / n_pair) * 8 + blockIdx.x % 8;
+    pair = slot % n_pair;
+  } else {
+    bh = blockIdx.x / n_pair;
+    pair = blockIdx.x % n_pair;
+  }
+}
+
+// The three kernels run one wave per SIMD, so nothing hides a wave's own latencies.  The work
+// on one block of keys (queries) is laid out by hand as three phases,
+//   P1  MFMAs that produce scores (row fragments of the streamed tiles from LDS)
+//   V   the vector work on the scores
+//   P3  MFMAs that consume the packed probabilities (transpose-read fragments)
+// and inside P1 and P3 every MFMA is followed by the LDS read of a fragment needed LEAD MFMAs
+// later (sched_barrier pins that order), so the matrix core never waits for an LDS round trip.
+// P1's last reads fetch P3's first fragments; P3's last reads fetch the next P1's first rows.
+// MFMAs that accumulate into the same registers are kept two slots apart.
+
 // ---------------------------------------------------------------------------------------------
-// Forward.  grid (S/128, B*H); wave w owns queries 128 qt + 32 w .. + 31; 64-key tiles.
+// Forward.  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
+// K and V stream through two LDS buffers.  Per tile: P1 = S^T for both 32-key halves, V = online
+// softmax over the 64 keys, P3 = O^T += V^T P^T.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ ctx, float* __restrict__ lse) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
+  constexpr int N = 2 * KS;            // MFMAs per phase (P3: 2 halves x 2 k-steps x DT = 2 KS as well)
+  constexpr int LEAD = N < 8 ? N : 8;  // fragments in flight
+  constexpr int NSEG = DH / 32;        // 1 KB load instructions per wave per tile
   extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 x [K tile | V tile]
-  const int qt = gridDim.x - 1 - blockIdx.x;                   // longest rows first
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int n_qt = S / 128;
+  int pair, bh;
+  pair_of_tiles(n_qt, BH, pair, bh);
+  const int b = bh / H, h = bh % H;
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
   const float scale = rsqrtf((float)DH);
+  const float c = scale * LOG2E;
+  const unsigned sm = lds_addr(smem);
 
-  bf16x8 qf[KS];
+  for (int pass = 0; pass < 2; pass++) {
+    const int qt = pass == 0 ? n_qt - 1 - pair : pair;  // the long one first
+    if (pass == 1 && qt == n_qt - 1 - pair) break;      // odd number of tiles: the middle one stands alone
+    const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
+    bf16x8 qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++)
-    qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
+    for (int ks = 0; ks < KS; ks++)
+      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) settle(qf[ks]);
+    float m = -INFINITY, l = 0.f;
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) oacc[dt][v] = 0.f;
 
-  float m = -INFINITY, l = 0.f;
-  f32x16 oacc[DT];
+    const int n_kv = 2 * (qt + 1);
+    auto tile_load = [&](int j0, int buf, int i) {
+      const unsigned st = sm + buf * 2 * TB;
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
+    };
+    bf16x8 fr[LEAD], fc[LEAD];
+    // One 64-key tile.  MASK: the tile may reach past the wave's first query.
+    auto tile = [&](auto mask_c, int t) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      const char* kt_ = smem + (t & 1) * 2 * TB;
+      const char* vt_ = kt_ + TB;
+      const int j0 = t * TR;
+      const int j0n = min(t + 1, n_kv - 1) * TR;  // past the end: the last tile again, into the buffer nobody reads
+      auto row_frag = [&](int i) { return frag_rows<DH>(kt_, (i % 2) * 32, i / 2, lane); };
+      // P3 slot i: d-tile dt = i % DT (so that MFMAs on the same accumulator are DT slots apart),
+      // then key half jt and k-step hh from i / DT
+      auto col_frag = [&](int i) {
+        return frag_cols<DH>(vt_, (i % DT) * 32, ((i / DT) % 2) * 32 + ((i / DT) / 2) * 16, lane);
+      };
 #pragma unroll
-  for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) oacc[dt][v] = 0.f;
-
-  auto step = [&](const char* kt, const char* vt, int j0) {
-    if (j0 > q0w + 31) return;  // every key of this tile is in the future of this wave's queries
-    f32x16 s[2];
-#pragma unroll
-    for (int jt = 0; jt < 2; jt++) {
-#pragma unroll
-      for (int v = 0; v < 16; v++) s[jt][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++)
-        s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(kt, jt * 32, ks, lane), qf[ks], s[jt], 0, 0, 0);
-    }
-    // Scores stay unscaled; the softmax scale rides in the exponent: p = 2^(c s - c m), c = scale log2 e.
-    const bool diag = j0 + 63 > q0w;
-    const float c = scale * LOG2E;
-    float mx = -INFINITY;
-    if (diag) {
+      for (int i = 0; i < LEAD; i++) fr[i] = row_frag(i);  // cold start: exposed once per tile
+      f32x16 s[2];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const int key = j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-          if (key > iq) s[jt][v] = -INFINITY;
-          mx = fmaxf(mx, s[jt][v]);
-        }
-    } else {
+        for (int v = 0; v < 16; v++) s[jt][v] = 0.f;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        s[i % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], s[i % 2], 0, 0, 0);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(i + LEAD);
+        else fc[i + LEAD - N] = col_frag(i + LEAD - N);
+        if (i < 2 * NSEG) tile_load(j0n, (t + 1) & 1, i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // Scores stay unscaled; the softmax scale rides in the exponent: p = 2^(c s - c m), c = scale log2 e.
+      if (MASK) {
+#pragma unroll
+        for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) {
+            const int key = j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+            if (key > iq) s[jt][v] = -INFINITY;
+          }
+      }
+      float mx = -INFINITY;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[jt][v]);
-    }
-    mx = fmaxf(mx, xor32(mx));
-    const float mn = fmaxf(m, mx);  // finite: key j0 <= q0w is visible to every query of the wave
-    const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
-    const float mc = mn * c;
-    float rs = 0.f;
+      mx = fmaxf(mx, xor32(mx));
+      const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and comes in the first tile
+      const float mc = mn * c;
+      float rs = 0.f;
+      bf16x8 pb[2][2];
 #pragma unroll
-    for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[jt][v], c, -mc));
-        s[jt][v] = p;
-        rs += p;
-      }
-    rs += xor32(rs);
-    l = l * corr + rs;
-    m = mn;
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
-#pragma unroll
-    for (int jt = 0; jt < 2; jt++)
-#pragma unroll
-      for (int hh = 0; hh < 2; hh++) {
-        const bf16x8 pb = pack8(s[jt], hh);
+        for (int v = 0; v < 16; v++) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[jt][v], c, -mc));
+          rs += p;
+          pb[jt][v >> 3][v & 7] = (__bf16)p;
+        }
+      rs += xor32(rs);
+      // The running maximum settles after the first few tiles; rescale the accumulators only
+      // when some query of the wave actually moved it.
+      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {
+        const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
+        l *= corr;
 #pragma unroll
         for (int dt = 0; dt < DT; dt++)
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(vt, dt * 32, jt * 32 + hh * 16, lane), pb,
-                                                             oacc[dt], 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
       }
-  };
+      l += rs;
+      m = mn;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        const int dt = i % DT;
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], pb[(i / DT) % 2][(i / DT) / 2], oacc[dt], 0, 0, 0);
+        if (i + LEAD < N) fc[i % LEAD] = col_frag(i + LEAD);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      lds_dma_wait();
+      __syncthreads();
+    };
 
-  const int n_kv = 2 * (qt + 1);
-  const unsigned sm = lds_addr(smem);
-  tile_dma<DH>(sm, base + Hd, ld);
-  tile_dma<DH>(sm + TB, base + 2 * Hd, ld);
-  lds_dma_wait();
-  __syncthreads();
-  for (int t = 0; t < n_kv - 1; t++) {
-    const char* cur = smem + (t & 1) * 2 * TB;
-    const unsigned nxt = sm + ((t + 1) & 1) * 2 * TB;
-    tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
-    tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
-    step(cur, cur + TB, t * TR);
+#pragma unroll
+    for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
     lds_dma_wait();
-  __syncthreads();
-  }
-  {
-    const char* cur = smem + ((n_kv - 1) & 1) * 2 * TB;
-    step(cur, cur + TB, (n_kv - 1) * TR);
-  }
+    __syncthreads();
+    for (int t = 0; t < n_kv - 2; t++) tile(F_{}, t);
+    tile(T_{}, n_kv - 2);  // the last two tiles (128 keys) straddle the diagonal of this workgroup's 128 queries
+    tile(T_{}, n_kv - 1);
 
-  store_rows<DH>(ctx + ((size_t)b * S + iq) * Hd + h * DH, oacc, 1.f / l, g);
-  if (g == 0) lse[((size_t)b * H + h) * S + iq] = m * scale + logf(l);
+    store_rows<DH>(ctx + ((size_t)b * S + iq) * Hd + h * DH, oacc, 1.f / l, g);
+    if (g == 0) lse[((size_t)b * H + h) * S + iq] = m * scale + logf(l);
+  }  // pass
 }
 
 // ---------------------------------------------------------------------------------------------
-// dQ.  Same decomposition as the forward pass; K and V tiles in LDS.
+// dQ.  Same decomposition as the forward pass; K and V tiles in LDS.  Per 32-key half:
+// P1 = S^T and dP^T (alternating), V = dS^T = P^T (dP^T - delta), P3 = dQ^T += K^T dS^T.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta,
                                                                const bf16_t* __restrict__ dctx,
                                                                bf16_t* __restrict__ dqkv) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  constexpr int N = 2 * KS;            // MFMAs in P1
+  constexpr int N3 = 2 * DT;           // MFMAs in P3 (= KS)
+  constexpr int LEAD = N < 8 ? N : 8;  // fragments in flight (>= N3)
+  constexpr int NSEG = DH / 32;
+  static_assert(N3 <= LEAD, "P1's tail prefetches all of P3's fragments");
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 x [K tile | V tile]
+  const int n_qt = S / 128;
+  int pair, bh;
+  pair_of_tiles(n_qt, BH, pair, bh);
+  const int b = bh / H, h = bh % H;
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
   const float scale = rsqrtf((float)DH);
+  const float c = scale * LOG2E;
+  const unsigned sm = lds_addr(smem);
 
-  bf16x8 qf[KS], dof[KS];
-  const bf16_t* dorow = dctx + ((size_t)b * S + iq) * Hd + h * DH;
+  for (int pass = 0; pass < 2; pass++) {
+    const int qt = pass == 0 ? n_qt - 1 - pair : pair;
+    if (pass == 1 && qt == n_qt - 1 - pair) break;
+    const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
+    bf16x8 qf[KS], dof[KS];
+    const bf16_t* dorow = dctx + ((size_t)b * S + iq) * Hd + h * DH;
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
-    dof[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dorow + ks * 16 + g * 8));
-  }
-  const float li = lse[((size_t)b * H + h) * S + iq] * LOG2E;
-  const float di = delta[((size_t)b * H + h) * S + iq];
-
-  f32x16 dq[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
-
-  auto step = [&](const char* kt, const char* vt, int j0) {
-    if (j0 > q0w + 31) return;
-    f32x16 s[2], dp[2];
-#pragma unroll
-    for (int jt = 0; jt < 2; jt++) {
-#pragma unroll
-      for (int v = 0; v < 16; v++) s[jt][v] = dp[jt][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(kt, jt * 32, ks, lane), qf[ks], s[jt], 0, 0, 0);
-        dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(vt, jt * 32, ks, lane), dof[ks], dp[jt], 0, 0, 0);
-      }
+    for (int ks = 0; ks < KS; ks++) {
+      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
+      dof[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dorow + ks * 16 + g * 8));
     }
-    const bool diag = j0 + 63 > q0w;
+    float li = lse[((size_t)b * H + h) * S + iq] * LOG2E;
+    float di = delta[((size_t)b * H + h) * S + iq];
 #pragma unroll
-    for (int jt = 0; jt < 2; jt++)
+    for (int ks = 0; ks < KS; ks++) { settle(qf[ks]); settle(dof[ks]); }
+    settle(li); settle(di);
+    f32x16 dq[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
+
+    const int n_kv = 2 * (qt + 1);
+    auto tile_load = [&](int j0, int buf, int i) {
+      const unsigned st = sm + buf * 2 * TB;
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
+    };
+    bf16x8 fr[LEAD], fc[LEAD];
+    // One half (32 keys, jt = 0 or 1) of the tile in `st`; fr[] holds its first LEAD row fragments.
+    auto half = [&](auto mask_c, auto next_c, auto load_c, const char* st, int jt, int j0, int j0n, int bufn) {
+      constexpr bool MASK = decltype(mask_c)::value, NEXT = decltype(next_c)::value, LOAD = decltype(load_c)::value;
+      const char* kt_ = st;
+      const char* vt_ = st + TB;
+      auto row_frag = [&](int jtx, int i) { return frag_rows<DH>(i % 2 ? vt_ : kt_, jtx * 32, i / 2, lane); };
+      auto col_frag = [&](int i) { return frag_cols<DH>(kt_, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
+      f32x16 sc, dp;
+#pragma unroll
+      for (int v = 0; v < 16; v++) sc[v] = dp[v] = 0.f;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        if (i % 2 == 0) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], sc, 0, 0, 0);
+        else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], dof[i / 2], dp, 0, 0, 0);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(jt, i + LEAD);
+        else if (i + LEAD - N < N3) fc[i + LEAD - N] = col_frag(i + LEAD - N);
+        if (LOAD && i < 2 * NSEG) tile_load(j0n, bufn, i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      bf16x8 db[2];
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        const int key = j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-        float p = __builtin_amdgcn_exp2f(s[jt][v] * (scale * LOG2E) - li);
-        if (diag && key > iq) p = 0.f;
-        s[jt][v] = p * (dp[jt][v] - di);
+        float p = __builtin_amdgcn_exp2f(fmaf(sc[v], c, -li));
+        if (MASK && j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3) > iq) p = 0.f;
+        db[v >> 3][v & 7] = (__bf16)(p * (dp[v] - di));
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int jt = 0; jt < 2; jt++)
-#pragma unroll
-      for (int hh = 0; hh < 2; hh++) {
-        const bf16x8 db = pack8(s[jt], hh);
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++)
-          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(kt, dt * 32, jt * 32 + hh * 16, lane), db, dq[dt],
-                                                           0, 0, 0);
+      for (int i = 0; i < N3; i++) {
+        dq[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i], db[i / DT], dq[i % DT], 0, 0, 0);
+        if (NEXT && i < LEAD) fr[i] = row_frag(jt + 1, i);
+        __builtin_amdgcn_sched_barrier(0);
       }
-  };
+      if (NEXT) {
+#pragma unroll
+        for (int i = N3; i < LEAD; i++) fr[i] = row_frag(jt + 1, i);
+      }
+    };
+    auto tile = [&](auto mask_c, int t) {
+      const char* st = smem + (t & 1) * 2 * TB;
+      const int j0n = min(t + 1, n_kv - 1) * TR;
+#pragma unroll
+      for (int i = 0; i < LEAD; i++) fr[i] = frag_rows<DH>(i % 2 ? st + TB : st, 0, i / 2, lane);
+      half(mask_c, T_{}, T_{}, st, 0, t * TR, j0n, (t + 1) & 1);
+      half(mask_c, F_{}, F_{}, st, 1, t * TR, j0n, (t + 1) & 1);
+      lds_dma_wait();
+      __syncthreads();
+    };
 
-  const int n_kv = 2 * (qt + 1);
-  const unsigned sm = lds_addr(smem);
-  tile_dma<DH>(sm, base + Hd, ld);
-  tile_dma<DH>(sm + TB, base + 2 * Hd, ld);
-  lds_dma_wait();
-  __syncthreads();
-  for (int t = 0; t < n_kv - 1; t++) {
-    const char* cur = smem + (t & 1) * 2 * TB;
-    const unsigned nxt = sm + ((t + 1) & 1) * 2 * TB;
-    tile_dma<DH>(nxt, base + (size_t)(t + 1) * TR * ld + Hd, ld);  // lands while this tile is computed
-    tile_dma<DH>(nxt + TB, base + (size_t)(t + 1) * TR * ld + 2 * Hd, ld);
-    step(cur, cur + TB, t * TR);
+#pragma unroll
+    for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
     lds_dma_wait();
-  __syncthreads();
-  }
-  {
-    const char* cur = smem + ((n_kv - 1) & 1) * 2 * TB;
-    step(cur, cur + TB, (n_kv - 1) * TR);
-  }
-  store_rows<DH>(dqkv + ((size_t)b * S + iq) * ld + h * DH, dq, scale, g);
+    __syncthreads();
+    for (int t = 0; t < n_kv - 2; t++) tile(F_{}, t);
+    tile(T_{}, n_kv - 2);
+    tile(T_{}, n_kv - 1);
+
+    store_rows<DH>(dqkv + ((size_t)b * S + iq) * ld + h * DH, dq, scale, g);
+  }  // pass
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK, dV.  grid (S/128, B*H); wave w owns keys 128 kt + 32 w .. + 31; 64-query tiles of Q and
-// dO (plus their lse and delta) stream through LDS, starting at the diagonal.
+// dK, dV.  1-D grid of (S/128) * B*H workgroups; wave w owns keys 128 kt + 32 w .. + 31, held in
+// registers as the B operands; 64-query tiles of Q and dO (plus their lse and delta) stream
+// through two LDS buffers, starting at the diagonal.
+//
+// Per 32-query half:
+//   P1  2 KS MFMAs: S = Q K^T and dP = dO V^T, alternating (row fragments of Q and dO)
+//   V   P = 2^(c S - lse log2 e), dS = P (dP - delta), both packed to bf16
+//   P3  2 KS MFMAs: dV^T += dO^T P and dK^T += Q^T dS, alternating (transpose-read fragments)
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta,
                                                                 const bf16_t* __restrict__ dctx,
                                                                 bf16_t* __restrict__ dqkv) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
   constexpr int STAGE = 2 * TB + 2 * TR * 4;  // Q tile | dO tile | lse[64] | delta[64]
+  constexpr int N = 2 * KS;                   // MFMAs per phase
+  constexpr int LEAD = N < 8 ? N : 8;         // fragments in flight
+  constexpr int NSEG = DH / 32;               // 1 KB load instructions per wave per tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int kt = blockIdx.x;  // key tile 0 sees every query: longest first
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int n_kt = S / 128;
+  int pair, bh;
+  pair_of_tiles(n_kt, BH, pair, bh);
+  const int b = bh / H, h = bh % H;
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
@@ -340,104 +457,126 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, co
   const float* lrow = lse + ((size_t)b * H + h) * S;
   const float* drow = delta + ((size_t)b * H + h) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
-  const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
-  const float scale = rsqrtf((float)DH);
+  const float c = rsqrtf((float)DH) * LOG2E;
+  const unsigned sm = lds_addr(smem);
 
+  for (int pass = 0; pass < 2; pass++) {
+  const int kt = pass == 0 ? pair : n_kt - 1 - pair;
+  if (pass == 1 && kt == pair) break;  // odd number of key tiles: the middle one stands alone
+  const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
     kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + Hd + ks * 16 + g * 8));
     vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + 2 * Hd + ks * 16 + g * 8));
   }
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) { settle(kf[ks]); settle(vf[ks]); }
   f32x16 dk[DT], dv[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
     for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
 
-  // One 64-query tile, as two halves of 32 so that only one half's scores are live at a time.
-  auto step = [&](const char* qt_, const char* dot_, const float* ls, const float* ds_, int i0) {
-    if (i0 + 63 < j0w) return;  // every query of this tile precedes this wave's keys
-    const bool diag = i0 < j0w + 31;
-#pragma unroll
-    for (int it = 0; it < 2; it++) {
-      f32x16 s, dp;
-#pragma unroll
-      for (int v = 0; v < 16; v++) s[v] = dp[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(qt_, it * 32, ks, lane), kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(dot_, it * 32, ks, lane), vf[ks], dp, 0, 0, 0);
-      }
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int r0 = it * 32 + q * 8 + g * 4;
-        const float4 l4 = *reinterpret_cast<const float4*>(ls + r0);   // lse * log2(e), pre-scaled on the way in
-        const float4 d4 = *reinterpret_cast<const float4*>(ds_ + r0);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-          const int v = q * 4 + r;
-          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale * LOG2E, -lv[r]));
-          if (diag && jk > i0 + r0 + r) p = 0.f;
-          s[v] = p;
-          dp[v] = p * (dp[v] - dvv[r]);
-        }
-      }
-#pragma unroll
-      for (int hh = 0; hh < 2; hh++) {
-        const bf16x8 pb = pack8(s, hh), db = pack8(dp, hh);
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(dot_, dt * 32, it * 32 + hh * 16, lane), pb,
-                                                           dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(qt_, dt * 32, it * 32 + hh * 16, lane), db,
-                                                           dk[dt], 0, 0, 0);
-        }
-      }
-    }
-  };
-
   const int i_first = kt * 128;
   const int n_q = (S - i_first) / TR;
-  float rl = 0.f, rdl = 0.f;
-  const unsigned sm = lds_addr(smem);
-  auto load = [&](int i0, int buf) {
-    tile_dma<DH>(sm + buf * STAGE, base + (size_t)i0 * ld, ld);
-    tile_dma<DH>(sm + buf * STAGE + TB, dob + (size_t)i0 * Hd, (size_t)Hd);
-    if (threadIdx.x < TR) {
-      rl = lrow[i0 + threadIdx.x] * LOG2E;
-      rdl = drow[i0 + threadIdx.x];
+  // Tile of queries i0.. into buffer `buf`: this wave's NSEG + NSEG segments of Q and dO (one per
+  // call, i = 0 .. 2 NSEG - 1), and the 64 lse and delta values (i == 2 NSEG; waves 0 and 1,
+  // 16 lanes x 16 bytes each).
+  auto tile_load = [&](int i0, int buf, int i) {
+    const unsigned st = sm + buf * STAGE;
+    if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, i);
+    else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, i - NSEG);
+    else if (wave < 2 && lane < 16) lds_dma16((wave == 0 ? lrow : drow) + i0 + lane * 4, st + 2 * TB + wave * (TR * 4));
+  };
+
+  bf16x8 fr[LEAD], fc[LEAD];
+  // One half (32 queries, it = 0 or 1) of the tile in `st`.  fr[] holds its first LEAD row
+  // fragments on entry.  MASK: the half may reach above the diagonal for this wave's keys.
+  // NEXT: prefetch the first row fragments of the tile's other half during P3.  LOAD: spread the
+  // load instructions of tile i0n -> buffer bufn over the first slots of P1.
+  auto half = [&](auto mask_c, auto next_c, auto load_c, const char* st, int it, int i0, int i0n, int bufn) {
+    constexpr bool MASK = decltype(mask_c)::value, NEXT = decltype(next_c)::value, LOAD = decltype(load_c)::value;
+    const char* qt_ = st;
+    const char* dot_ = st + TB;
+    auto row_frag = [&](int itx, int i) { return frag_rows<DH>(i % 2 ? dot_ : qt_, itx * 32, i / 2, lane); };
+    auto col_frag = [&](int i) {
+      return frag_cols<DH>(i % 2 ? qt_ : dot_, ((i / 2) % DT) * 32, it * 32 + (i / (2 * DT)) * 16, lane);
+    };
+    // the lse and delta values of the four row groups this lane meets in its accumulators
+    float4 l4[4], d4[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      l4[q] = *reinterpret_cast<const float4*>(st + 2 * TB + (it * 32 + q * 8 + g * 4) * 4);
+      d4[q] = *reinterpret_cast<const float4*>(st + 2 * TB + TR * 4 + (it * 32 + q * 8 + g * 4) * 4);
+    }
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; v++) s[v] = dp[v] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      if (i % 2 == 0) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], kf[i / 2], s, 0, 0, 0);
+      else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], vf[i / 2], dp, 0, 0, 0);
+      if (i + LEAD < N) fr[i % LEAD] = row_frag(it, i + LEAD);
+      else fc[i + LEAD - N] = col_frag(i + LEAD - N);
+      if (LOAD && i <= 2 * NSEG) tile_load(i0n, bufn, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    bf16x8 pb[2], db[2];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const float lv[4] = {l4[q].x, l4[q].y, l4[q].z, l4[q].w}, dl[4] = {d4[q].x, d4[q].y, d4[q].z, d4[q].w};
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int v = q * 4 + r;
+        float p = __builtin_amdgcn_exp2f(fmaf(s[v], c, -LOG2E * lv[r]));
+        if (MASK && jk > i0 + it * 32 + q * 8 + g * 4 + r) p = 0.f;
+        const float d = p * (dp[v] - dl[r]);
+        pb[v >> 3][v & 7] = (__bf16)p;
+        db[v >> 3][v & 7] = (__bf16)d;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      const int hh = i / (2 * DT), dt = (i / 2) % DT;
+      if (i % 2 == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], pb[hh], dv[dt], 0, 0, 0);
+      else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], db[hh], dk[dt], 0, 0, 0);
+      if (i + LEAD < N) fc[i % LEAD] = col_frag(i + LEAD);
+      else if (NEXT) fr[i + LEAD - N] = row_frag(it + 1, i + LEAD - N);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto store = [&](char* st) {
-    if (threadIdx.x < TR) {
-      reinterpret_cast<float*>(st + 2 * TB)[threadIdx.x] = rl;
-      reinterpret_cast<float*>(st + 2 * TB + TR * 4)[threadIdx.x] = rdl;
-    }
+  // One tile: the fragment pipeline starts cold (its first reads are exposed once per tile); the
+  // next tile is requested while this one is computed and published by the barrier at the end.
+  auto tile = [&](auto mask_c, int t) {
+    const char* st = smem + (t & 1) * STAGE;
+    const int i0 = i_first + t * TR;
+    const int i0n = i_first + min(t + 1, n_q - 1) * TR;  // past the end: the last tile again, into the buffer nobody reads
+#pragma unroll
+    for (int i = 0; i < LEAD; i++) fr[i] = frag_rows<DH>(i % 2 ? st + TB : st, 0, i / 2, lane);
+    half(mask_c, T_{}, T_{}, st, 0, i0, i0n, (t + 1) & 1);
+    half(mask_c, F_{}, F_{}, st, 1, i0, i0n, (t + 1) & 1);
+    lds_dma_wait();
+    __syncthreads();
   };
-  load(i_first, 0);
-  store(smem);
+
+#pragma unroll
+  for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first, 0, i);
   lds_dma_wait();
   __syncthreads();
-  for (int t = 0; t < n_q - 1; t++) {
-    const char* cur = smem + (t & 1) * STAGE;
-    char* nxt = smem + ((t + 1) & 1) * STAGE;
-    load(i_first + (t + 1) * TR, (t + 1) & 1);
-    step(cur, cur + TB, reinterpret_cast<const float*>(cur + 2 * TB), reinterpret_cast<const float*>(cur + 2 * TB + TR * 4),
-         i_first + t * TR);
-    store(nxt);
-    lds_dma_wait();
-  __syncthreads();
-  }
-  {
-    const char* cur = smem + ((n_q - 1) & 1) * STAGE;
-    step(cur, cur + TB, reinterpret_cast<const float*>(cur + 2 * TB), reinterpret_cast<const float*>(cur + 2 * TB + TR * 4),
-         i_first + (n_q - 1) * TR);
-  }
+  // the first two tiles (128 queries) straddle the diagonal of this workgroup's 128 keys
+  tile(T_{}, 0);
+  tile(T_{}, 1);
+  for (int t = 2; t < n_q; t++) tile(F_{}, t);
+  lds_dma_wait();
+
+  const float scale = rsqrtf((float)DH);
   bf16_t* out = dqkv + ((size_t)b * S + jk) * ld + h * DH;
   store_rows<DH>(out + Hd, dk, scale, g);
   store_rows<DH>(out + 2 * Hd, dv, 1.f, g);
+  }  // pass
 }
 
 bool attn_mfma_supported(int dtype, int B, int S, int H, int dh) {
@@ -455,7 +594,8 @@ template <int DH>
 static int fwd_t(int B, int S, int H, const bf16_t* qkv, bf16_t* ctx, float* lse, hipStream_t s) {
   constexpr size_t lds = 4 * (size_t)TR * DH * 2;
   FAX_TRY(set_lds(attn_fwd_mfma_kernel<DH>, lds));
-  hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH>), dim3(S / 128, B * H), dim3(256), lds, s, S, H, qkv, ctx, lse);
+  hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds, s, S, H, B * H, qkv, ctx,
+                     lse);
   FAX_LAUNCH_CHECK("attn_fwd_mfma");
   return FAX_OK;
 }
@@ -472,10 +612,10 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const float* lse, const
   constexpr size_t lds_kv = 2 * (2 * (size_t)TR * DH * 2 + 2 * TR * 4);
   FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
   FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), dim3(S / 128, B * H), dim3(256), lds_kv, s, S, H, qkv, lse, delta,
-                     dctx, dqkv);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), dim3(S / 128, B * H), dim3(256), lds_q, s, S, H, qkv, lse, delta, dctx,
-                     dqkv);
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds_kv, s, S, H, B * H, qkv, lse,
+                     delta, dctx, dqkv);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds_q, s, S, H, B * H, qkv,
+                     lse, delta, dctx, dqkv);
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;
 }
