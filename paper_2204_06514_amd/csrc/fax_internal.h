@@ -189,6 +189,11 @@ __device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lan
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                : : "s"(lds_segment_addr), "v"(lane_byte_offset), "s"(uniform_base) : "memory");
 }
+// 4 bytes per lane: the wave's 256 bytes land at M0 + 4 * lane.
+__device__ __forceinline__ void lds_dma4(const void* global_src, unsigned lds_segment_addr) {
+  const unsigned dst = __builtin_amdgcn_readfirstlane(lds_segment_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(dst), "v"(global_src) : "memory");
+}
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- GEMM epilogue shared by the scalar and MFMA kernels ----

@@ -18,9 +18,12 @@
 // exactly what two ds_read_b64_tr_b16 deliver for the matching A operand.
 //
 // LDS tiles are [64 rows][DH] bf16 with the 16-byte chunk index XOR-ed by
-// f(row) = ((row & 3) << 1) | ((row >> 2) & 1): 8 consecutive rows land in 8 distinct chunks
-// (128-bit row-fragment reads) and 4 consecutive rows in 4 distinct 32-byte pairs (transpose
-// reads), so one copy of a tile serves both access patterns.
+// f(row) = ((row & 3) << 1) | ((row >> 2) & 1), plus (row & 8) when a row has 16 chunks:
+// consecutive rows land in distinct chunks (128-bit row-fragment reads) and 4 consecutive rows in
+// 4 distinct 32-byte pairs (transpose reads), so one copy of a tile serves both access patterns.
+// Measured on gfx950 with 256-byte rows: row-fragment reads 122 B/clk/CU with the (row & 8) term,
+// 102 without; transpose reads 77 B/clk/CU either way (55 unswizzled) -- ds_read_b64_tr_b16 tops
+// out at about 60 % of the plain read rate.
 //
 // No atomics: dQ has one writer per query row, dK/dV one writer per key row; S and dP are
 // recomputed in both backward kernels (7 tile products instead of 5).
@@ -35,17 +38,22 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+template <int V> using I = std::integral_constant<int, V>;
 using T_ = std::true_type;
 using F_ = std::false_type;
 
 static constexpr float LOG2E = 1.4426950408889634f;
 static constexpr int TR = 64;  // rows per LDS tile
 
-__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+template <int DH>
+__device__ __forceinline__ int swz(int row) {
+  const int f = ((row & 3) << 1) | ((row >> 2) & 1);
+  return DH >= 128 ? f | (row & 8) : f;  // 16 chunks per row: 16 consecutive rows in 16 distinct chunks
+}
 
 template <int DH>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
-  return row * (DH * 2) + ((chunk ^ swz(row)) << 4);
+  return row * (DH * 2) + ((chunk ^ swz<DH>(row)) << 4);
 }
 
 // A 64 x DH tile moved global -> LDS directly (global_load_lds_dwordx4: no staging registers, no
@@ -62,7 +70,7 @@ __device__ __forceinline__ void tile_dma(unsigned lds, const bf16_t* __restrict_
   for (int i = 0; i < DH / 32; i++) {
     const int seg = wave * (DH / 32) + i;  // which 1 KB segment of the tile
     const int row = seg * RPI + lane / NCH;
-    const int chunk = (lane % NCH) ^ swz(row);
+    const int chunk = (lane % NCH) ^ swz<DH>(row);
     lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
   }
 }
@@ -128,7 +136,7 @@ __device__ __forceinline__ void tile_dma_seg(unsigned lds, const bf16_t* __restr
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int seg = wave * (DH / 32) + i;
   const int row = seg * RPI + lane / NCH;
-  const int chunk = (lane % NCH) ^ swz(row);
+  const int chunk = (lane % NCH) ^ swz<DH>(row);
   lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
 }
 
@@ -311,8 +319,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, int BH
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                                const float* __restrict__ lse,
-                                                               const float* __restrict__ delta,
+                                                               const bf16_t* __restrict__ ctx,
                                                                const bf16_t* __restrict__ dctx,
+                                                               float* __restrict__ delta,
                                                                bf16_t* __restrict__ dqkv) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
   constexpr int N = 2 * KS;            // MFMAs in P1
@@ -345,7 +354,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
       dof[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dorow + ks * 16 + g * 8));
     }
     float li = lse[((size_t)b * H + h) * S + iq] * LOG2E;
-    float di = delta[((size_t)b * H + h) * S + iq];
+    // delta_i = sum_d dO[i, d] O[i, d]: this lane holds half of row i of dO (the d's of its k-slots);
+    // its partner lane (lane ^ 32) holds the other half.  Also stored for the dK/dV kernel.
+    float di = 0.f;
+    const bf16_t* orow = ctx + ((size_t)b * S + iq) * Hd + h * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const bf16x8 o = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(orow + ks * 16 + g * 8));
+#pragma unroll
+      for (int e = 0; e < 8; e++) di = fmaf((float)o[e], (float)dof[ks][e], di);
+    }
+    di += xor32(di);
+    if (g == 0) delta[((size_t)b * H + h) * S + iq] = di;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) { settle(qf[ks]); settle(dof[ks]); }
     settle(li); settle(di);
@@ -425,15 +445,24 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK, dV.  1-D grid of (S/128) * B*H workgroups; wave w owns keys 128 kt + 32 w .. + 31, held in
-// registers as the B operands; 64-query tiles of Q and dO (plus their lse and delta) stream
-// through two LDS buffers, starting at the diagonal.
-//
-// Per 32-query half:
-//   P1  2 KS MFMAs: S = Q K^T and dP = dO V^T, alternating (row fragments of Q and dO)
-//   V   P = 2^(c S - lse log2 e), dS = P (dP - delta), both packed to bf16
-//   P3  2 KS MFMAs: dV^T += dO^T P and dK^T += Q^T dS, alternating (transpose-read fragments)
+// dK, dV.  Wave w owns keys 128 kt + 32 w .. + 31, held in registers as the B operands; 64-query
+// tiles of Q and dO (plus their lse and delta) stream through three LDS buffers, starting at the
+// diagonal.  Per 32-query half u:
+//   S(u) = Q K^T and dP(u) = dO V^T, alternating (row fragments of Q and dO)
+//   V(u): P = 2^(c S - lse log2 e), dS = P (dP - delta), both packed to bf16
+//   P3(u): dV^T += dO^T P and dK^T += Q^T dS, alternating (transpose-read fragments)
+// The vector work is about as long as one of the MFMA phases, so it is hidden behind the score
+// MFMAs of the *next* half: the loop body is
+//   C(u)  = slot by slot: one MFMA of S/dP(u+1), one fragment read, one element of V(u)
+//   P3(u) = slot by slot: one MFMA of dV/dK(u), one fragment read (the tile loads ride here too)
+// with two sets of score accumulators taking turns.  Past the last half the "next" scores are
+// computed from the last half again and dropped, which keeps the loop body free of special cases.
+// One barrier per tile, before P3 of the tile's first half: it publishes the next tile (first
+// needed by the row prefetch at the end of that P3) and frees the buffer of the previous one,
+// into which the tile after next is then requested.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float f4_get(const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; }
+
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                                 const float* __restrict__ lse,
@@ -441,10 +470,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, in
                                                                 const bf16_t* __restrict__ dctx,
                                                                 bf16_t* __restrict__ dqkv) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  constexpr int STAGE = 2 * TB + 2 * TR * 4;  // Q tile | dO tile | lse[64] | delta[64]
+  // Q tile | dO tile | per wave w: lse[16 w .. +15], delta[16 w .. +15], and a copy of both (the
+  // 64 lanes of one 4-byte load instruction: 32 useful values, fetched twice)
+  constexpr int LD_OFF = 2 * TB, STAGE = 2 * TB + 4 * 256, NBUF = 3;
   constexpr int N = 2 * KS;                   // MFMAs per phase
   constexpr int LEAD = N < 8 ? N : 8;         // fragments in flight
-  constexpr int NSEG = DH / 32;               // 1 KB load instructions per wave per tile
+  constexpr int NSEG = DH / 32;               // 1 KB load instructions per wave per tile and operand
+  constexpr int EPS = 16 / N;                 // score elements per slot of C
+  static_assert(16 % N == 0 && 2 * NSEG + 1 <= N && 8 <= N, "slot plan");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n_kt = S / 128;
   int pair, bh;
@@ -456,126 +489,146 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, in
   const bf16_t* dob = dctx + (size_t)b * S * Hd + h * DH;
   const float* lrow = lse + ((size_t)b * H + h) * S;
   const float* drow = delta + ((size_t)b * H + h) * S;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const int lane = threadIdx.x & 63, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const float c = rsqrtf((float)DH) * LOG2E;
   const unsigned sm = lds_addr(smem);
 
   for (int pass = 0; pass < 2; pass++) {
-  const int kt = pass == 0 ? pair : n_kt - 1 - pair;
-  if (pass == 1 && kt == pair) break;  // odd number of key tiles: the middle one stands alone
-  const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
-  bf16x8 kf[KS], vf[KS];
+    const int kt = pass == 0 ? pair : n_kt - 1 - pair;
+    if (pass == 1 && kt == pair) break;  // odd number of key tiles: the middle one stands alone
+    const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
+    bf16x8 kf[KS], vf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + Hd + ks * 16 + g * 8));
-    vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + 2 * Hd + ks * 16 + g * 8));
-  }
+    for (int ks = 0; ks < KS; ks++) {
+      kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + Hd + ks * 16 + g * 8));
+      vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + 2 * Hd + ks * 16 + g * 8));
+    }
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) { settle(kf[ks]); settle(vf[ks]); }
-  f32x16 dk[DT], dv[DT];
+    for (int ks = 0; ks < KS; ks++) { settle(kf[ks]); settle(vf[ks]); }
+    f32x16 dk[DT], dv[DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; dt++)
+    for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-    for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
+      for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
 
-  const int i_first = kt * 128;
-  const int n_q = (S - i_first) / TR;
-  // Tile of queries i0.. into buffer `buf`: this wave's NSEG + NSEG segments of Q and dO (one per
-  // call, i = 0 .. 2 NSEG - 1), and the 64 lse and delta values (i == 2 NSEG; waves 0 and 1,
-  // 16 lanes x 16 bytes each).
-  auto tile_load = [&](int i0, int buf, int i) {
-    const unsigned st = sm + buf * STAGE;
-    if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, i);
-    else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, i - NSEG);
-    else if (wave < 2 && lane < 16) lds_dma16((wave == 0 ? lrow : drow) + i0 + lane * 4, st + 2 * TB + wave * (TR * 4));
-  };
-
-  bf16x8 fr[LEAD], fc[LEAD];
-  // One half (32 queries, it = 0 or 1) of the tile in `st`.  fr[] holds its first LEAD row
-  // fragments on entry.  MASK: the half may reach above the diagonal for this wave's keys.
-  // NEXT: prefetch the first row fragments of the tile's other half during P3.  LOAD: spread the
-  // load instructions of tile i0n -> buffer bufn over the first slots of P1.
-  auto half = [&](auto mask_c, auto next_c, auto load_c, const char* st, int it, int i0, int i0n, int bufn) {
-    constexpr bool MASK = decltype(mask_c)::value, NEXT = decltype(next_c)::value, LOAD = decltype(load_c)::value;
-    const char* qt_ = st;
-    const char* dot_ = st + TB;
-    auto row_frag = [&](int itx, int i) { return frag_rows<DH>(i % 2 ? dot_ : qt_, itx * 32, i / 2, lane); };
-    auto col_frag = [&](int i) {
-      return frag_cols<DH>(i % 2 ? qt_ : dot_, ((i / 2) % DT) * 32, it * 32 + (i / (2 * DT)) * 16, lane);
+    const int i_first = kt * 128;
+    const int n_q = (S - i_first) / TR, n_half = 2 * n_q;
+    // Tile of queries i0.. into buffer `buf`, one load instruction per call: this wave's NSEG
+    // segments of Q (i < NSEG), of dO (i < 2 NSEG), and its 16 lse and 16 delta values.
+    auto tile_load = [&](int i0, int buf, int i) {
+      const unsigned st = sm + buf * STAGE;
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, i);
+      else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, i - NSEG);
+      else lds_dma4(((lane & 16) ? drow : lrow) + i0 + wave * 16 + (lane & 15), st + LD_OFF + wave * 256);
     };
-    // the lse and delta values of the four row groups this lane meets in its accumulators
+    auto stage = [&](int t) { return smem + (min(t, n_q - 1) % NBUF) * STAGE; };  // past the end: the last tile again
+    auto row_frag = [&](const char* st, int it, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, it * 32, i / 2, lane); };
+    auto col_frag = [&](const char* st, int it, int i) {
+      return frag_cols<DH>(i % 2 ? st : st + TB, ((i / 2) % DT) * 32, it * 32 + (i / (2 * DT)) * 16, lane);
+    };
+    // lse / delta of the rows 32 it + 8 q + 4 g + 0..3 that this lane meets in accumulator group q
+    auto stat4 = [&](const char* st, int it, int q, int which) {
+      const int row = it * 32 + q * 8 + g * 4;
+      return *reinterpret_cast<const float4*>(st + LD_OFF + (row >> 4) * 256 + which * 64 + (row & 15) * 4);
+    };
+
+    bf16x8 fr[LEAD], fc[LEAD];
+    f32x16 sc[2], dp[2];  // [u & 1]: scores of half u
     float4 l4[4], d4[4];
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      l4[q] = *reinterpret_cast<const float4*>(st + 2 * TB + (it * 32 + q * 8 + g * 4) * 4);
-      d4[q] = *reinterpret_cast<const float4*>(st + 2 * TB + TR * 4 + (it * 32 + q * 8 + g * 4) * 4);
-    }
-    f32x16 s, dp;
-#pragma unroll
-    for (int v = 0; v < 16; v++) s[v] = dp[v] = 0.f;
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < N; i++) {
-      if (i % 2 == 0) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], kf[i / 2], s, 0, 0, 0);
-      else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], vf[i / 2], dp, 0, 0, 0);
-      if (i + LEAD < N) fr[i % LEAD] = row_frag(it, i + LEAD);
-      else fc[i + LEAD - N] = col_frag(i + LEAD - N);
-      if (LOAD && i <= 2 * NSEG) tile_load(i0n, bufn, i);
-      __builtin_amdgcn_sched_barrier(0);
-    }
     bf16x8 pb[2], db[2];
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // MFMA i of S/dP for the half whose row fragments are in flight, into score set `par`
+    auto score_mfma = [&](int par, int i) {
+      if (i % 2 == 0) sc[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], kf[i / 2], i < 2 ? zero : sc[par], 0, 0, 0);
+      else dp[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], vf[i / 2], i < 2 ? zero : dp[par], 0, 0, 0);
+    };
+    // Half u (it = u & 1 fixed at compile time): C(u), [barrier], P3(u).
+    auto step = [&](auto mask_c, auto it_c, int u) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      constexpr int IT = decltype(it_c)::value;
+      const int t = u >> 1;
+      const char* st = stage(t);                    // tile of half u
+      const char* st1 = stage((u + 1) >> 1);        // ... of half u + 1
+      const char* st2 = stage(t + 1);               // ... of half u + 2
+      const int i0h = i_first + t * TR + IT * 32;   // first query of half u
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const float lv[4] = {l4[q].x, l4[q].y, l4[q].z, l4[q].w}, dl[4] = {d4[q].x, d4[q].y, d4[q].z, d4[q].w};
+      for (int i = 0; i < N; i++) {
+        score_mfma(IT ^ 1, i);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(st1, IT ^ 1, i + LEAD);
+        else fc[i + LEAD - N] = col_frag(st, IT, i + LEAD - N);
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int v = q * 4 + r;
-        float p = __builtin_amdgcn_exp2f(fmaf(s[v], c, -LOG2E * lv[r]));
-        if (MASK && jk > i0 + it * 32 + q * 8 + g * 4 + r) p = 0.f;
-        const float d = p * (dp[v] - dl[r]);
-        pb[v >> 3][v & 7] = (__bf16)p;
-        db[v >> 3][v & 7] = (__bf16)d;
+        for (int e = 0; e < EPS; e++) {
+          const int v = i * EPS + e, q = v >> 2, r = v & 3;
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[IT][v], c, -LOG2E * f4_get(l4[q], r)));
+          if (MASK && jk > i0h + q * 8 + g * 4 + r) p = 0.f;
+          const float d = p * (dp[IT][v] - f4_get(d4[q], r));
+          pb[v >> 3][v & 7] = (__bf16)p;
+          db[v >> 3][v & 7] = (__bf16)d;
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-    }
-    __builtin_amdgcn_sched_barrier(0);
+      if (IT == 0) {
+        // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
+        // half u - 1, the last reader of tile t - 1
+        lds_dma_wait();
+        __syncthreads();
+      }
+      const int i0n = i_first + min(t + 2, n_q - 1) * TR;
 #pragma unroll
-    for (int i = 0; i < N; i++) {
-      const int hh = i / (2 * DT), dt = (i / 2) % DT;
-      if (i % 2 == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], pb[hh], dv[dt], 0, 0, 0);
-      else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], db[hh], dk[dt], 0, 0, 0);
-      if (i + LEAD < N) fc[i % LEAD] = col_frag(i + LEAD);
-      else if (NEXT) fr[i + LEAD - N] = row_frag(it + 1, i + LEAD - N);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  // One tile: the fragment pipeline starts cold (its first reads are exposed once per tile); the
-  // next tile is requested while this one is computed and published by the barrier at the end.
-  auto tile = [&](auto mask_c, int t) {
-    const char* st = smem + (t & 1) * STAGE;
-    const int i0 = i_first + t * TR;
-    const int i0n = i_first + min(t + 1, n_q - 1) * TR;  // past the end: the last tile again, into the buffer nobody reads
+      for (int i = 0; i < N; i++) {
+        const int hh = i / (2 * DT), dt = (i / 2) % DT;
+        if (i % 2 == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], pb[hh], dv[dt], 0, 0, 0);
+        else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], db[hh], dk[dt], 0, 0, 0);
+        if (i + LEAD < N) fc[i % LEAD] = col_frag(st, IT, i + LEAD);
+        else fr[i + LEAD - N] = row_frag(st2, IT, i + LEAD - N);
+        if (i < 8) {  // statistics of half u + 1, for the next C
+          if (i < 4) l4[i] = stat4(st1, IT ^ 1, i, 0);
+          else d4[i - 4] = stat4(st1, IT ^ 1, i - 4, 1);
+        }
+        if (IT == 0 && i <= 2 * NSEG) tile_load(i0n, (t + 2) % NBUF, i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+
 #pragma unroll
-    for (int i = 0; i < LEAD; i++) fr[i] = frag_rows<DH>(i % 2 ? st + TB : st, 0, i / 2, lane);
-    half(mask_c, T_{}, T_{}, st, 0, i0, i0n, (t + 1) & 1);
-    half(mask_c, F_{}, F_{}, st, 1, i0, i0n, (t + 1) & 1);
+    for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first, 0, i);
+#pragma unroll
+    for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first + TR, 1, i);
     lds_dma_wait();
     __syncthreads();
-  };
-
+    // scores of half 0, cold: fragment reads exposed once per pass
+    {
+      const char* st = stage(0);
 #pragma unroll
-  for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first, 0, i);
-  lds_dma_wait();
-  __syncthreads();
-  // the first two tiles (128 queries) straddle the diagonal of this workgroup's 128 keys
-  tile(T_{}, 0);
-  tile(T_{}, 1);
-  for (int t = 2; t < n_q; t++) tile(F_{}, t);
-  lds_dma_wait();
+      for (int i = 0; i < LEAD; i++) fr[i] = row_frag(st, 0, i);
+#pragma unroll
+      for (int q = 0; q < 4; q++) { l4[q] = stat4(st, 0, q, 0); d4[q] = stat4(st, 0, q, 1); }
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        score_mfma(0, i);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(st, 0, i + LEAD);
+        else fr[i + LEAD - N] = row_frag(st, 1, i + LEAD - N);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // the first two tiles (four halves) straddle the diagonal of this workgroup's 128 keys
+    step(T_{}, I<0>{}, 0);
+    step(T_{}, I<1>{}, 1);
+    step(T_{}, I<0>{}, 2);
+    step(T_{}, I<1>{}, 3);
+    for (int u = 4; u < n_half; u += 2) {
+      step(F_{}, I<0>{}, u);
+      step(F_{}, I<1>{}, u + 1);
+    }
+    lds_dma_wait();   // the re-requested last tile
+    __syncthreads();  // LDS is reused by the next pass
 
-  const float scale = rsqrtf((float)DH);
-  bf16_t* out = dqkv + ((size_t)b * S + jk) * ld + h * DH;
-  store_rows<DH>(out + Hd, dk, scale, g);
-  store_rows<DH>(out + 2 * Hd, dv, 1.f, g);
+    const float scale = rsqrtf((float)DH);
+    bf16_t* out = dqkv + ((size_t)b * S + jk) * ld + h * DH;
+    store_rows<DH>(out + Hd, dk, scale, g);
+    store_rows<DH>(out + 2 * Hd, dv, 1.f, g);
   }  // pass
 }
 
@@ -606,26 +659,25 @@ int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float
 }
 
 template <int DH>
-static int bwd_t(int B, int S, int H, const bf16_t* qkv, const float* lse, const float* delta, const bf16_t* dctx,
-                 bf16_t* dqkv, hipStream_t s) {
+static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx,
+                 bf16_t* dqkv, float* delta, hipStream_t s) {
   constexpr size_t lds_q = 4 * (size_t)TR * DH * 2;
-  constexpr size_t lds_kv = 2 * (2 * (size_t)TR * DH * 2 + 2 * TR * 4);
+  constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);
   FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
   FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds_kv, s, S, H, B * H, qkv, lse,
-                     delta, dctx, dqkv);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds_q, s, S, H, B * H, qkv,
-                     lse, delta, dctx, dqkv);
+  const dim3 grid(((S / 128 + 1) / 2) * B * H);
+  // dQ first: it also produces delta, which the dK/dV kernel reads
+  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;
 }
 
 int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse, const void* dctx,
                   void* dqkv, float* delta, hipStream_t s) {
-  FAX_TRY(attn_delta(FAX_BF16, B, S, H, dh, ctx, dctx, delta, s));
   if (dh == 64)
-    return bwd_t<64>(B, S, H, (const bf16_t*)qkv, lse, delta, (const bf16_t*)dctx, (bf16_t*)dqkv, s);
-  return bwd_t<128>(B, S, H, (const bf16_t*)qkv, lse, delta, (const bf16_t*)dctx, (bf16_t*)dqkv, s);
+    return bwd_t<64>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s);
+  return bwd_t<128>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s);
 }
 
 }  // namespace fax
