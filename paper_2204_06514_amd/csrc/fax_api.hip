@@ -280,11 +280,12 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   float* delta = (float*)(ws + W.delta);
   void* red = ws + W.red;
 
-  auto wgrad = [&](const void* act, int lda, int Kdim, const void* grad, int ldb, int Ndim, void* out) {
-    GemmArgs g;  // out[Kdim, Ndim] (+)= act^T grad, contraction over the T rows
+  auto wgrad = [&](const void* act, int lda, int Kdim, const void* grad, int ldb, int Ndim, void* out, void* bias_grad) {
+    GemmArgs g;  // out[Kdim, Ndim] (+)= act^T grad, contraction over the T rows; bias_grad[Ndim] (+)= column sums of grad
     g.dtype = d.dtype; g.ta = true; g.tb = false;
     g.M = Kdim; g.N = Ndim; g.K = T;
     g.A = act; g.lda = lda; g.B = grad; g.ldb = ldb; g.C = out; g.ldc = Ndim; g.c_f32 = true; g.accumulate = acc;
+    g.colsum = (float*)bias_grad; g.colsum_ws = red;
     return gemm(g, s);
   };
   auto dgrad = [&](const void* grad, int lda, int Ndim, const void* w, int ldw, int Kdim, void* out) {
@@ -296,30 +297,26 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   };
 
   // feed-forward output projection
-  FAX_TRY(colsum(d.dtype, T, D, dy, D, (float*)gr.b2, acc, red, s));
-  FAX_TRY(wgrad(saved + L.a, F, F, dy, D, D, gr.w2));
+  FAX_TRY(wgrad(saved + L.a, F, F, dy, D, D, gr.w2, gr.b2));
   {
     GemmArgs g = dgrad(dy, D, D, p.w2, D, F, du);  // du = (dy W2^T) * gelu'(u)
     g.epi = EPI_DGELU; g.U = saved + L.u; g.ldu = F; g.gelu_form = d.gelu;
     FAX_TRY(gemm(g, s));
   }
   // feed-forward input projection
-  FAX_TRY(colsum(d.dtype, T, F, du, F, (float*)gr.b1, acc, red, s));
-  FAX_TRY(wgrad(saved + L.h2, D, D, du, F, F, gr.w1));
+  FAX_TRY(wgrad(saved + L.h2, D, D, du, F, F, gr.w1, gr.b1));
   FAX_TRY(gemm(dgrad(du, F, F, p.w1, F, D, dh2), s));
   // LN2 and the residual branch: dx1 = dy + LN2'(dh2)
   FAX_TRY(ln_bwd(d.dtype, T, D, dh2, saved + L.x1, (const float*)(saved + L.mu2), (const float*)(saved + L.rstd2),
                  p.ln2_g, dy, dx1, (float*)gr.ln2_g, (float*)gr.ln2_b, acc, red, s));
   // attention output projection
-  FAX_TRY(colsum(d.dtype, T, D, dx1, D, (float*)gr.bo, acc, red, s));
-  FAX_TRY(wgrad(saved + L.ctx, Hd, Hd, dx1, D, D, gr.wo));
+  FAX_TRY(wgrad(saved + L.ctx, Hd, Hd, dx1, D, D, gr.wo, gr.bo));
   FAX_TRY(gemm(dgrad(dx1, D, D, p.wo, D, Hd, dctx), s));
   // attention
   FAX_TRY(attention_bwd(d.dtype, d.B, d.S, d.H, d.dh, saved + L.qkv, saved + L.ctx, (const float*)(saved + L.lse), dctx,
                         dqkv, delta, PATH_AUTO, s));
   // QKV projection
-  FAX_TRY(colsum(d.dtype, T, 3 * Hd, dqkv, 3 * Hd, (float*)gr.bqkv, acc, red, s));
-  FAX_TRY(wgrad(saved + L.h1, D, D, dqkv, 3 * Hd, 3 * Hd, gr.wqkv));
+  FAX_TRY(wgrad(saved + L.h1, D, D, dqkv, 3 * Hd, 3 * Hd, gr.wqkv, gr.bqkv));
   FAX_TRY(gemm(dgrad(dqkv, 3 * Hd, 3 * Hd, p.wqkv, 3 * Hd, D, dh1), s));
   // LN1 and the residual branch: dx = dx1 + LN1'(dh1)
   FAX_TRY(ln_bwd(d.dtype, T, D, dh1, x, (const float*)(saved + L.mu1), (const float*)(saved + L.rstd1), p.ln1_g, dx1,

@@ -52,6 +52,11 @@ struct GemmArgs {
   const void* U = nullptr; int ldu = 0;
   int gelu_form = FAX_GELU_TANH;
   int path = PATH_AUTO;
+  // Optional by-product, B stored [K, N] only: colsum[n] (+)= sum over k of B[k, n] (`accumulate`
+  // applies to it as well).  colsum_ws: colsum_ws_bytes(N) of scratch for the paths that take the
+  // sums in a separate pass.
+  float* colsum = nullptr;
+  void* colsum_ws = nullptr;
 };
 int gemm(const GemmArgs& g, hipStream_t s);
 int gemm_simt(const GemmArgs& g, hipStream_t s);
@@ -204,6 +209,7 @@ struct EpiArgs {
   void* C2; int ldc2;
   const void* U; int ldu;
   int epi, gelu_form, c_f32, accumulate;
+  float* colsum;
 };
 
 template <typename T>

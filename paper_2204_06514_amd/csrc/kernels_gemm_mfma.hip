@@ -30,6 +30,7 @@
 namespace fax {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -88,7 +89,8 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
 enum { EK_STORE = 0, EK_GELU_TANH = 1, EK_GELU_ERF = 2, EK_DGELU_TANH = 3, EK_DGELU_ERF = 4, EK_F32 = 5 };
 enum {
   EM_RES = 8,  // bf16 kinds: add the residual R;  EK_F32: add to what C already holds
-  EM_C2 = 16   // EK_STORE: also write the plain product (before bias and residual) to C2
+  EM_C2 = 16,  // EK_STORE: also write the plain product (before bias and residual) to C2
+  EM_COLSUM = 32  // EK_F32, B stored [K, N]: also colsum[n] (+)= sum_k B[k, n]
 };
 constexpr int em_kind(int em) { return em & 7; }
 constexpr bool em_dgelu(int em) { return em_kind(em) == EK_DGELU_TANH || em_kind(em) == EK_DGELU_ERF; }
@@ -262,6 +264,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   constexpr int SLOTS_A = 2 * NSLOT;             // slots open to the A loads
   constexpr int SLOTS_B = NSLOT - PB + NSLOT;    // ... and to the B loads
   static_assert(NSA <= SLOTS_A && NSB <= SLOTS_B && NSA < 64, "load schedule");
+  // Optional by-product (EM_COLSUM, B stored [K, N]): colsum[n] (+)= sum over k of B[k, n], which for
+  // a weight-gradient product is the bias gradient.  Every workgroup sweeps all of K, so the
+  // workgroups of tile row 0 between them see every column of B in full; their waves add up the
+  // B fragments they feed to the matrix core anyway (lane = column, 8 k's per fragment).  The
+  // two waves that share a column range (wm = 0 and wm != 0) take alternate elements, one
+  // element per wave and slot at 256^2, and combine through LDS after the loop.  The main loop
+  // exists in three copies (no sums, even elements, odd elements) so that the other workgroups
+  // pay nothing and the element indices stay compile-time constants.
+  constexpr bool CS = (EM & EM_COLSUM) != 0;
+  static_assert(!CS || !B_KC, "column sums are taken from [K, N] fragments");
+  const bool cs_on = CS && tm_i == 0;
+  const int cs_half = wm != 0;
+  float cs[TN];
+#pragma unroll
+  for (int j = 0; j < TN; j++) cs[j] = 0.f;
+  auto main_loop = [&](auto cs_c, auto half_c) {
+  constexpr bool CSON = decltype(cs_c)::value;
+  constexpr int CS_HALF = decltype(half_c)::value;  // which element of each pair this wave sums
+  constexpr int EPSL = 8 * TN / NSLOT;  // fragment elements summed per slot
+  static_assert(EPSL % 2 == 0, "two waves share the elements of a slot");
   bf16x8 fa[2][TM], fb[2][TN];
   // Slots [T0, T1) of one phase: MFMA t on fragment buffer USE, then fragment read t of k-step ks
   // from (srcA, srcB) into buffer USE ^ 1 (when LOADF), then the slab loads that the schedule
@@ -276,6 +298,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     for (int t = T0; t < T1; t++) {
       const int i = t / TN, j = t % TN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[USE][j], fa[USE][i], acc[i][j], 0, 0, 0);  // C^T tile
+      if (CSON) {  // this wave's half of the slot's elements: the wave with the other wm takes the rest
+#pragma unroll
+        for (int k = 0; k < EPSL / 2; k++) {
+          const int el = t * EPSL + 2 * k + CS_HALF;
+          cs[el / 8] += (float)fb[USE][el / 8][el % 8];
+        }
+      }
       if (LOADF) {
         if (t < TM) fa[USE ^ 1][t] = frag_load<BM, A_KC>(srcA, wm + t * 32, ks, lane);
         else if (t < TM + TN) fb[USE ^ 1][t - TM] = frag_load<BN, B_KC>(srcB, wn + (t - TM) * 32, ks, lane);
@@ -325,6 +354,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     phase(I<0>{}, T_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 3, 0, 0);
     phase(I<1>{}, F_{}, I<0>{}, I<0>{}, I<0>{}, I<NSLOT>{}, curA, curB, 0, 0, 0);
   }
+  };  // main_loop
+  if constexpr (CS) {
+    if (!cs_on) main_loop(F_{}, I<0>{});
+    else if (cs_half) main_loop(T_{}, I<1>{});
+    else main_loop(T_{}, I<0>{});
+  } else {
+    main_loop(F_{}, I<0>{});
+  }
   lds_dma_wait();  // the re-requested last slab: nothing may be in flight when LDS is reused or the wave ends
 
   // Epilogue.  Each wave turns 64 rows of its tile at a time through its own quarter of LDS
@@ -342,6 +379,27 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   static_assert(NIT % BATCH == 0, "batching of the read-back");
   __syncthreads();                // every wave is done with the operand slabs
   float* wbuf = reinterpret_cast<float*>(smem) + wave * 64 * WC;
+  if constexpr (CS) {
+    if (cs_on) {  // uniform over the workgroup
+      // lanes l and l ^ 32 hold different k's of the same column; waves wm = 0 and wm != 0 different elements
+      float* xch = reinterpret_cast<float*>(smem) + 4 * 64 * WC + (wave & 1) * (TN * 32);  // past every wave's wbuf
+#pragma unroll
+      for (int j = 0; j < TN; j++) cs[j] += __shfl_xor(cs[j], 32, 64);
+      if (cs_half && lane < 32) {
+#pragma unroll
+        for (int j = 0; j < TN; j++) xch[j * 32 + lane] = cs[j];
+      }
+      __syncthreads();
+      if (!cs_half && lane < 32) {
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          const float v = cs[j] + xch[j * 32 + lane];
+          float* o = e.colsum + n0 + wn + j * 32 + lane;
+          *o = e.accumulate ? *o + v : v;
+        }
+      }
+    }
+  }
   const int c4 = (lane % LPR) * 4;
   const int rsub = lane / LPR;
   const int ncol = n0 + wn + c4;
@@ -415,6 +473,7 @@ static int pick_tile(const GemmArgs& g) {
 bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.dtype != FAX_BF16) return false;
   if (g.c_f32 && (g.bias || g.R || g.C2 || g.epi != EPI_NONE)) return false;  // fp32 C is the plain weight-gradient form
+  if (g.colsum && !(g.c_f32 && g.ta && !g.tb)) return false;  // the column sums of B ride only on that form, A [K, M], B [K, N]
   // the GELU epilogues exist for the orientations the block uses them in: forward (A [M,K], B [K,N])
   // and input-gradient (A [M,K], B [N,K])
   if (g.epi == EPI_GELU && (g.ta || g.tb || g.R)) return false;
@@ -457,6 +516,9 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
     return erf ? launch_mfma<BT, true, false, EK_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EK_GELU_TANH>(g, e, s);
   if (g.epi == EPI_DGELU)
     return erf ? launch_mfma<BT, true, true, EK_DGELU_ERF>(g, e, s) : launch_mfma<BT, true, true, EK_DGELU_TANH>(g, e, s);
+  if (g.c_f32 && g.colsum)
+    return g.accumulate ? launch_mfma<BT, false, false, EK_F32 | EM_RES | EM_COLSUM>(g, e, s)
+                        : launch_mfma<BT, false, false, EK_F32 | EM_COLSUM>(g, e, s);
   if (g.c_f32) {
     if (g.accumulate) {
       if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_F32 | EM_RES>(g, e, s);
@@ -486,7 +548,7 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
 
 int gemm_mfma(const GemmArgs& g, hipStream_t s) {
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
-            g.accumulate ? 1 : 0};
+            g.accumulate ? 1 : 0, g.colsum};
   if (pick_tile(g) == 256) return dispatch<256>(g, e, s);
   return dispatch<128>(g, e, s);
 }

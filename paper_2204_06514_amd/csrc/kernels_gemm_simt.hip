@@ -105,15 +105,20 @@ int gemm(const GemmArgs& g, hipStream_t s) {
 }
 
 static int gemm_dispatch(const GemmArgs& g, hipStream_t s) {
-  if (g.path == PATH_SIMT) return gemm_simt(g, s);
-  if (g.path == PATH_MFMA) {
-    if (!gemm_mfma_supported(g)) {
-      set_error("fax_gemm: shape M=%d N=%d K=%d (dtype %d) does not tile for the MFMA kernel", g.M, g.N, g.K, g.dtype);
-      return FAX_ERR_UNSUPPORTED;
-    }
-    return gemm_mfma(g, s);
+  const bool mfma = g.path != PATH_SIMT && gemm_mfma_supported(g);
+  if (g.path == PATH_MFMA && !mfma) {
+    set_error("fax_gemm: shape M=%d N=%d K=%d (dtype %d) does not tile for the MFMA kernel", g.M, g.N, g.K, g.dtype);
+    return FAX_ERR_UNSUPPORTED;
   }
-  if (gemm_mfma_supported(g)) return gemm_mfma(g, s);
+  if (mfma) return gemm_mfma(g, s);
+  if (g.colsum) {
+    // no fused form here: take the column sums of B [K, N] in a pass of their own
+    if (g.tb || !g.colsum_ws) {
+      set_error("gemm: column sums need B stored [K, N] and scratch space");
+      return FAX_ERR_INVALID_ARG;
+    }
+    FAX_TRY(colsum(g.dtype, g.K, g.N, g.B, g.ldb, g.colsum, g.accumulate, g.colsum_ws, s));
+  }
   return gemm_simt(g, s);
 }
 
