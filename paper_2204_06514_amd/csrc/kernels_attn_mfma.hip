@@ -313,8 +313,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(int S, int H, int BH
 }
 
 // ---------------------------------------------------------------------------------------------
-// dQ.  Same decomposition as the forward pass; K and V tiles in LDS.  Per 32-key half:
-// P1 = S^T and dP^T (alternating), V = dS^T = P^T (dP^T - delta), P3 = dQ^T += K^T dS^T.
+// dQ (and delta).  Wave w owns queries 128 qt + 32 w .. + 31 (Q and dO rows in registers as B
+// operands); 64-key tiles of K and V stream through three LDS buffers.  Per 32-key half u:
+//   S^T(u) = K Q^T and dP^T(u) = V dO^T, alternating (row fragments of K and V)
+//   V(u): dS^T = P^T (dP^T - delta), P^T = 2^(c S^T - lse log2 e), packed to bf16
+//   P3(u): dQ^T += K^T dS^T (transpose-read fragments of K)
+// laid out like the dK/dV kernel below: C(u) = score MFMAs of half u + 1 with V(u) riding on
+// them, then P3(u); one barrier per tile, before P3 of its first half.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
@@ -324,12 +329,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
                                                                float* __restrict__ delta,
                                                                bf16_t* __restrict__ dqkv) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  constexpr int N = 2 * KS;            // MFMAs in P1
-  constexpr int N3 = 2 * DT;           // MFMAs in P3 (= KS)
-  constexpr int LEAD = N < 8 ? N : 8;  // fragments in flight (>= N3)
+  constexpr int STAGE = 2 * TB, NBUF = 3;  // K tile | V tile
+  constexpr int N = 2 * KS;            // score MFMAs per half
+  constexpr int N3 = 2 * DT;           // dQ MFMAs per half (= KS)
+  constexpr int LEAD = N < 8 ? N : 8;  // fragments in flight
   constexpr int NSEG = DH / 32;
-  static_assert(N3 <= LEAD, "P1's tail prefetches all of P3's fragments");
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 x [K tile | V tile]
+  constexpr int EPS = 16 / N;          // score elements per slot of C
+  static_assert(N3 <= LEAD && 2 * NSEG <= N3 && 16 % N == 0, "slot plan");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n_qt = S / 128;
   int pair, bh;
   pair_of_tiles(n_qt, BH, pair, bh);
@@ -375,70 +382,94 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
 #pragma unroll
       for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
 
-    const int n_kv = 2 * (qt + 1);
+    const int n_kv = 2 * (qt + 1), n_half = 2 * n_kv;
     auto tile_load = [&](int j0, int buf, int i) {
-      const unsigned st = sm + buf * 2 * TB;
+      const unsigned st = sm + buf * STAGE;
       if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
       else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
     };
+    auto stage = [&](int t) { return smem + (min(t, n_kv - 1) % NBUF) * STAGE; };  // past the end: the last tile again
+    auto row_frag = [&](const char* st, int jt, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, jt * 32, i / 2, lane); };
+    auto col_frag = [&](const char* st, int jt, int i) { return frag_cols<DH>(st, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
+
     bf16x8 fr[LEAD], fc[LEAD];
-    // One half (32 keys, jt = 0 or 1) of the tile in `st`; fr[] holds its first LEAD row fragments.
-    auto half = [&](auto mask_c, auto next_c, auto load_c, const char* st, int jt, int j0, int j0n, int bufn) {
-      constexpr bool MASK = decltype(mask_c)::value, NEXT = decltype(next_c)::value, LOAD = decltype(load_c)::value;
-      const char* kt_ = st;
-      const char* vt_ = st + TB;
-      auto row_frag = [&](int jtx, int i) { return frag_rows<DH>(i % 2 ? vt_ : kt_, jtx * 32, i / 2, lane); };
-      auto col_frag = [&](int i) { return frag_cols<DH>(kt_, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
-      f32x16 sc, dp;
-#pragma unroll
-      for (int v = 0; v < 16; v++) sc[v] = dp[v] = 0.f;
-      __builtin_amdgcn_sched_barrier(0);
+    f32x16 sc[2], dp[2];  // [u & 1]: scores of half u
+    bf16x8 db[2];
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto score_mfma = [&](int par, int i) {
+      if (i % 2 == 0) sc[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], i < 2 ? zero : sc[par], 0, 0, 0);
+      else dp[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], dof[i / 2], i < 2 ? zero : dp[par], 0, 0, 0);
+    };
+    // Half u (jt = u & 1 fixed at compile time): C(u), [barrier], P3(u).
+    auto step = [&](auto mask_c, auto jt_c, int u) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      constexpr int JT = decltype(jt_c)::value;
+      const int t = u >> 1;
+      const char* st = stage(t);
+      const char* st1 = stage((u + 1) >> 1);
+      const char* st2 = stage(t + 1);
+      const int j0h = t * TR + JT * 32;  // first key of half u
 #pragma unroll
       for (int i = 0; i < N; i++) {
-        if (i % 2 == 0) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], sc, 0, 0, 0);
-        else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], dof[i / 2], dp, 0, 0, 0);
-        if (i + LEAD < N) fr[i % LEAD] = row_frag(jt, i + LEAD);
-        else if (i + LEAD - N < N3) fc[i + LEAD - N] = col_frag(i + LEAD - N);
-        if (LOAD && i < 2 * NSEG) tile_load(j0n, bufn, i);
+        score_mfma(JT ^ 1, i);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(st1, JT ^ 1, i + LEAD);
+        else if (i + LEAD - N < N3) fc[i + LEAD - N] = col_frag(st, JT, i + LEAD - N);
+#pragma unroll
+        for (int e = 0; e < EPS; e++) {
+          const int v = i * EPS + e;
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[JT][v], c, -li));
+          if (MASK && j0h + (v >> 2) * 8 + g * 4 + (v & 3) > iq) p = 0.f;
+          db[v >> 3][v & 7] = (__bf16)(p * (dp[JT][v] - di));
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
-      bf16x8 db[2];
-#pragma unroll
-      for (int v = 0; v < 16; v++) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sc[v], c, -li));
-        if (MASK && j0 + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3) > iq) p = 0.f;
-        db[v >> 3][v & 7] = (__bf16)(p * (dp[v] - di));
+      if (JT == 0) {
+        // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
+        // half u - 1, the last reader of tile t - 1
+        lds_dma_wait();
+        __syncthreads();
       }
-      __builtin_amdgcn_sched_barrier(0);
+      const int j0n = min(t + 2, n_kv - 1) * TR;
 #pragma unroll
       for (int i = 0; i < N3; i++) {
         dq[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i], db[i / DT], dq[i % DT], 0, 0, 0);
-        if (NEXT && i < LEAD) fr[i] = row_frag(jt + 1, i);
+        if (i < LEAD) fr[i] = row_frag(st2, JT, i);
+        if (JT == 0 && i < 2 * NSEG) tile_load(j0n, (t + 2) % NBUF, i);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (NEXT) {
 #pragma unroll
-        for (int i = N3; i < LEAD; i++) fr[i] = row_frag(jt + 1, i);
-      }
-    };
-    auto tile = [&](auto mask_c, int t) {
-      const char* st = smem + (t & 1) * 2 * TB;
-      const int j0n = min(t + 1, n_kv - 1) * TR;
-#pragma unroll
-      for (int i = 0; i < LEAD; i++) fr[i] = frag_rows<DH>(i % 2 ? st + TB : st, 0, i / 2, lane);
-      half(mask_c, T_{}, T_{}, st, 0, t * TR, j0n, (t + 1) & 1);
-      half(mask_c, F_{}, F_{}, st, 1, t * TR, j0n, (t + 1) & 1);
-      lds_dma_wait();
-      __syncthreads();
+      for (int i = N3; i < LEAD; i++) fr[i] = row_frag(st2, JT, i);
     };
 
 #pragma unroll
     for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
+#pragma unroll
+    for (int i = 0; i < 2 * NSEG; i++) tile_load(TR, 1, i);
     lds_dma_wait();
     __syncthreads();
-    for (int t = 0; t < n_kv - 2; t++) tile(F_{}, t);
-    tile(T_{}, n_kv - 2);
-    tile(T_{}, n_kv - 1);
+    {  // scores of half 0, cold: fragment reads exposed once per pass
+      const char* st = stage(0);
+#pragma unroll
+      for (int i = 0; i < LEAD; i++) fr[i] = row_frag(st, 0, i);
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        score_mfma(0, i);
+        if (i + LEAD < N) fr[i % LEAD] = row_frag(st, 0, i + LEAD);
+        else fr[i + LEAD - N] = row_frag(st, 1, i + LEAD - N);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    for (int u = 0; u < n_half - 4; u += 2) {
+      step(F_{}, I<0>{}, u);
+      step(F_{}, I<1>{}, u + 1);
+    }
+    // the last two tiles (four halves) straddle the diagonal of this workgroup's 128 queries
+    step(T_{}, I<0>{}, n_half - 4);
+    step(T_{}, I<1>{}, n_half - 3);
+    step(T_{}, I<0>{}, n_half - 2);
+    step(T_{}, I<1>{}, n_half - 1);
+    lds_dma_wait();   // the re-requested last tile
+    __syncthreads();  // LDS is reused by the next pass
 
     store_rows<DH>(dqkv + ((size_t)b * S + iq) * ld + h * DH, dq, scale, g);
   }  // pass
@@ -661,7 +692,7 @@ int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float
 template <int DH>
 static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx,
                  bf16_t* dqkv, float* delta, hipStream_t s) {
-  constexpr size_t lds_q = 4 * (size_t)TR * DH * 2;
+  constexpr size_t lds_q = 3 * (2 * (size_t)TR * DH * 2);
   constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);
   FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
   FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));

@@ -314,11 +314,15 @@ __global__ __launch_bounds__(256) void colsum_kernel(int rows, int N, const T* _
 }
 
 // out[n] (+)= sum_p partial[p * N + n], p < parts: 64 columns per block, 4 waves split the parts.
+// blockIdx.y = 1 folds a second stack of partials, stored right behind the first, into out1.
 __global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, const float* __restrict__ partial,
-                                                            float* __restrict__ out, int accumulate) {
+                                                            float* __restrict__ out0, float* __restrict__ out1,
+                                                            int accumulate) {
   __shared__ float red[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + lane;
+  partial += (size_t)blockIdx.y * parts * N;
+  float* out = blockIdx.y ? out1 : out0;
   float s = 0.f;
   if (n < N)
     for (int p = wave; p < parts; p += 4) s += partial[(size_t)p * N + n];
@@ -361,9 +365,7 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
                      mu, rstd, partial);
   FAX_LAUNCH_CHECK("ln_bwd_dgamma_dbeta");
   const int gb = (D + 63) / 64;
-  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, D, partial, dgamma, accumulate ? 1 : 0);
-  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb), dim3(256), 0, s, parts, D, partial + (size_t)parts * D, dbeta,
-                     accumulate ? 1 : 0);
+  hipLaunchKernelGGL(fold_partials_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
   FAX_LAUNCH_CHECK("ln_bwd_fold");
   return FAX_OK;
 }
@@ -395,7 +397,8 @@ int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool 
                        (const bf16_t*)nullptr, (const float*)nullptr, (const float*)nullptr, partial);
   }
   FAX_LAUNCH_CHECK("colsum");
-  hipLaunchKernelGGL(fold_partials_kernel, dim3((N + 63) / 64), dim3(256), 0, s, parts, N, partial, out, accumulate ? 1 : 0);
+  hipLaunchKernelGGL(fold_partials_kernel, dim3((N + 63) / 64), dim3(256), 0, s, parts, N, partial, out, (float*)nullptr,
+                     accumulate ? 1 : 0);
   FAX_LAUNCH_CHECK("colsum_fold");
   return FAX_OK;
 }
