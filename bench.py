@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (the same C-ABI calls) in a HIP graph and time its replays")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain elementwise copy kernel (reads 256 MiB, writes 128 MiB): a known-size reference "
                          "for the HBM byte counters")
@@ -142,12 +144,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    timed_step = step
+    if args.graph:
+        for _ in range(2):  # first calls set kernel attributes: keep them out of the capture
+            step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        timed_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
 

@@ -172,33 +172,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   constexpr int A_BUFS = 3, B_BUFS = 2;
   constexpr int B_BASE = A_BUFS * LA::BYTES;
 
-  // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with
-  // its own L2), so id is first re-dealt so that each XCD owns a contiguous run of tiles, then
-  // tiles are walked in column-major groups of 8 tile-rows to keep the working set of A and B
-  // panels small.
-  int id = blockIdx.x;
+  // Persistent workgroups: workgroup b works through tiles b, b + gridDim.x, ...  (the host
+  // launches one workgroup per CU, or fewer when there are fewer tiles).  The point is the seam
+  // between two tiles: the first slabs of the next tile are requested before the epilogue of the
+  // finished one, so their latency (about 3 us from a cold start) runs behind the epilogue.
+  //
+  // Tile number -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with
+  // its own L2) and gridDim.x is a multiple of 8 whenever that matters, so a workgroup's tile
+  // numbers all have its own residue mod 8; the number is first re-dealt so that each XCD owns a
+  // contiguous run of tiles, then tiles are walked in column-major groups of 8 tile-rows to keep
+  // the working set of A and B panels small.
   const int nt = tiles_m * tiles_n;
-  if (nt % 8 == 0) id = (id % 8) * (nt / 8) + id / 8;
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * tiles_n;
-  const int g = id / per_group;
-  const int gm0 = g * GROUP;
-  const int gsz = min(GROUP, tiles_m - gm0);
-  const int tm_i = gm0 + (id % per_group) % gsz;
-  const int tn_i = (id % per_group) / gsz;
-  const int m0 = tm_i * BM, n0 = tn_i * BN;
+  auto tile_of = [&](int id, int& tm_i, int& tn_i) {
+    if (nt % 8 == 0) id = (id % 8) * (nt / 8) + id / 8;
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * tiles_n;
+    const int g = id / per_group;
+    const int gm0 = g * GROUP;
+    const int gsz = min(GROUP, tiles_m - gm0);
+    tm_i = gm0 + (id % per_group) % gsz;
+    tn_i = (id % per_group) / gsz;
+  };
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // in a scalar register: LDS segment addresses stay scalar
   const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   // This wave's share of a slab: segments wave*NSEG .. +NSEG-1 of A and likewise of B.  Segment
   // q of a slab is bytes [1024 q, 1024 q + 1024) of its buffer; this lane's 16 bytes sit at
@@ -210,31 +208,53 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   for (int q = 0; q < NSA; q++) a_lane_off[q] = slab_lane_offset<BM, A_KC>(lda, (wave * NSA + q) * 1024 + lane * 16);
 #pragma unroll
   for (int q = 0; q < NSB; q++) b_lane_off[q] = slab_lane_offset<BN, B_KC>(ldb, (wave * NSB + q) * 1024 + lane * 16);
-  const bf16_t* const a_tile = A + (A_KC ? (size_t)m0 * lda : (size_t)m0);
-  const bf16_t* const b_tile = B + (B_KC ? (size_t)n0 * ldb : (size_t)n0);
   const size_t a_kstride = A_KC ? 1 : (size_t)lda, b_kstride = B_KC ? 1 : (size_t)ldb;
   const unsigned smem_addr = lds_addr(smem);
-  // segment q of the A (B) slab at k0 -> A (B) buffer number `buf`
-  auto dma_a = [&](int q, int k0, int buf) {
-    lds_dma16(a_tile + k0 * a_kstride, a_lane_off[q], smem_addr + buf * LA::BYTES + (wave * NSA + q) * 1024);
+  auto a_tile_of = [&](int tm_i) { return A + (A_KC ? (size_t)tm_i * BM * lda : (size_t)tm_i * BM); };
+  auto b_tile_of = [&](int tn_i) { return B + (B_KC ? (size_t)tn_i * BN * ldb : (size_t)tn_i * BN); };
+  // segment q of the A (B) slab at k0 of the tile at `tile_base` -> A (B) buffer number `buf`
+  auto dma_a_from = [&](const bf16_t* tile_base, int q, int k0, int buf) {
+    lds_dma16(tile_base + k0 * a_kstride, a_lane_off[q], smem_addr + buf * LA::BYTES + (wave * NSA + q) * 1024);
   };
-  auto dma_b = [&](int q, int k0, int buf) {
-    lds_dma16(b_tile + k0 * b_kstride, b_lane_off[q], smem_addr + B_BASE + buf * LB::BYTES + (wave * NSB + q) * 1024);
+  auto dma_b_from = [&](const bf16_t* tile_base, int q, int k0, int buf) {
+    lds_dma16(tile_base + k0 * b_kstride, b_lane_off[q], smem_addr + B_BASE + buf * LB::BYTES + (wave * NSB + q) * 1024);
+  };
+  const int nk = K / GK;
+  // A tile starts with slab 0 in A[0], B[0] and slab 1 in A[1], B[1].  Everything but B of slab 1
+  // can be requested while the previous tile's epilogue still uses A[2] and B[1].
+  auto request_first_slabs = [&](const bf16_t* a_base, const bf16_t* b_base) {
+#pragma unroll
+    for (int q = 0; q < NSA; q++) dma_a_from(a_base, q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < NSB; q++) dma_b_from(b_base, q, 0, 0);
+    if (nk > 1) {
+#pragma unroll
+      for (int q = 0; q < NSA; q++) dma_a_from(a_base, q, GK, 1);
+    }
   };
 
-  const int nk = K / GK;
-#pragma unroll
-  for (int q = 0; q < NSA; q++) dma_a(q, 0, 0);
-#pragma unroll
-  for (int q = 0; q < NSB; q++) dma_b(q, 0, 0);
+  int tm_i, tn_i;
+  tile_of(blockIdx.x, tm_i, tn_i);
+  request_first_slabs(a_tile_of(tm_i), b_tile_of(tn_i));
+  for (int tile = blockIdx.x; tile < nt; tile += gridDim.x) {
+  const int m0 = tm_i * BM, n0 = tn_i * BN;
+  const bf16_t* const a_tile = a_tile_of(tm_i);
+  const bf16_t* const b_tile = b_tile_of(tn_i);
+  auto dma_a = [&](int q, int k0, int buf) { dma_a_from(a_tile, q, k0, buf); };
+  auto dma_b = [&](int q, int k0, int buf) { dma_b_from(b_tile, q, k0, buf); };
+  lds_dma_wait();   // slab 0 and A of slab 1 (requested a whole epilogue ago, except for the first tile)
+  __syncthreads();  // ... are visible; every wave is done with the previous tile's epilogue staging
   if (nk > 1) {
 #pragma unroll
-    for (int q = 0; q < NSA; q++) dma_a(q, GK, 1);
-#pragma unroll
-    for (int q = 0; q < NSB; q++) dma_b(q, GK, 1);
+    for (int q = 0; q < NSB; q++) dma_b(q, GK, 1);  // B of slab 1: needed at the first in-loop barrier, waited for there
   }
-  lds_dma_wait();
-  __syncthreads();
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   // Software pipeline.  A slab is four k-steps ("phases") of TM x TN MFMAs each.  Operand
   // fragments are double buffered in registers: phase s issues the LDS reads for phase s+1.
@@ -364,25 +384,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   }
   lds_dma_wait();  // the re-requested last slab: nothing may be in flight when LDS is reused or the wave ends
 
-  // Epilogue.  Each wave turns 64 rows of its tile at a time through its own quarter of LDS
-  // (fp32) and reads them back row-wise, four consecutive columns per lane, so that a row of the
-  // wave tile leaves as one contiguous run and bias, residual and the GELU side inputs move as
-  // 8-byte vectors.  On the way in a lane writes the 16-byte units it owns (row l & 31); the
-  // 16-byte chunk index is XOR-ed with (row & 7) so that neither those writes (8 lanes = 8 rows,
-  // same chunk) nor the row-wise reads (8 lanes = 8 consecutive chunks) collide on LDS banks.
-  // Reads are issued eight rows ahead of the arithmetic and stores that consume them.
+  // Epilogue.  Each wave turns 32 rows of its tile at a time through LDS (fp32) and reads them
+  // back row-wise, four consecutive columns per lane, so that a row of the wave tile leaves as
+  // one contiguous run and bias, residual and the GELU side inputs move as 8-byte vectors.  On
+  // the way in a lane writes the 16-byte units it owns (row l & 31); the 16-byte chunk index is
+  // XOR-ed with (row & 7) so that neither those writes (8 lanes = 8 rows, same chunk) nor the
+  // row-wise reads (8 lanes = 8 consecutive chunks) collide on LDS banks.  Reads are issued eight
+  // rows ahead of the arithmetic and stores that consume them.  The staging areas are A[2] (waves
+  // 0, 1) and B[1] (waves 2, 3): A[0], A[1] and B[0] are already receiving the next tile.
   constexpr int WC = TN * 32;     // columns of the wave tile
   constexpr int LPR = WC / 4;     // lanes per row on the way out
   constexpr int RPI = 64 / LPR;   // rows per store instruction
-  constexpr int NIT = 64 / RPI;   // store instructions per 64 rows
-  constexpr int BATCH = 8;
+  constexpr int NIT = 32 / RPI;   // store instructions per 32 rows
+  constexpr int BATCH = NIT < 8 ? NIT : 8;
   static_assert(NIT % BATCH == 0, "batching of the read-back");
+  static_assert(2 * 32 * WC * 4 <= LA::BYTES && 2 * 32 * WC * 4 <= LB::BYTES, "two waves stage in one slab buffer");
   __syncthreads();                // every wave is done with the operand slabs
-  float* wbuf = reinterpret_cast<float*>(smem) + wave * 64 * WC;
+  float* wbuf = reinterpret_cast<float*>(smem + (wave < 2 ? 2 * LA::BYTES : B_BASE + LB::BYTES)) + (wave & 1) * 32 * WC;
   if constexpr (CS) {
     if (cs_on) {  // uniform over the workgroup
-      // lanes l and l ^ 32 hold different k's of the same column; waves wm = 0 and wm != 0 different elements
-      float* xch = reinterpret_cast<float*>(smem) + 4 * 64 * WC + (wave & 1) * (TN * 32);  // past every wave's wbuf
+      // lanes l and l ^ 32 hold different k's of the same column; waves wm = 0 and wm != 0 different
+      // elements.  Exchange through the start of the receiving wave's own staging area.
+      float* xch = reinterpret_cast<float*>(smem + 2 * LA::BYTES) + (wave & 1) * 32 * WC;
 #pragma unroll
       for (int j = 0; j < TN; j++) cs[j] += __shfl_xor(cs[j], 32, 64);
       if (cs_half && lane < 32) {
@@ -400,8 +423,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
       }
     }
   }
-  const int c4 = (lane % LPR) * 4;
-  const int rsub = lane / LPR;
+  // the next tile's first slabs, before anything else of the epilogue
+  if (tile + (int)gridDim.x < nt) {
+    tile_of(tile + gridDim.x, tm_i, tn_i);
+    request_first_slabs(a_tile_of(tm_i), b_tile_of(tn_i));
+  }
+  // (lane index through an opaque copy: otherwise everything derived from it below is hoisted out of
+  // the tile loop and kept in registers across the main loop, which has none to spare)
+  int lane_e = lane;
+  asm volatile("" : "+v"(lane_e));
+  const int c4 = (lane_e % LPR) * 4;
+  const int rsub = lane_e / LPR;
   const int ncol = n0 + wn + c4;
   constexpr bool F32 = em_kind(EM) == EK_F32, DG = em_dgelu(EM);
   constexpr bool SIDE = !F32 && (DG || (EM & EM_RES));  // a bf16 side input: pre-activation U or residual R
@@ -409,28 +441,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   if (!F32 && e.bias) bias = ld_bf16x4(e.bias, ncol);
   const bf16_t* sp = (const bf16_t*)(DG ? e.U : e.R);
   const int lds_ = DG ? e.ldu : e.ldr;
-#pragma unroll
-  for (int half = 0; half < TM / 2; half++) {
-    const int mrow = m0 + wm + half * 64 + rsub;
-    // request the side input of all 64 rows first: the loads fly while the tile turns through LDS
-    bf16x4 side[SIDE ? NIT : 1];
+  // the side input of 32 rows is requested one round ahead: the loads fly while the previous
+  // rows turn through LDS
+  bf16x4 side[2][SIDE ? NIT : 1];
+  auto side_request = [&](int i, bf16x4 (&dst)[SIDE ? NIT : 1]) {
     if (SIDE) {
 #pragma unroll
       for (int k = 0; k < NIT; k++)
-        side[k] = *reinterpret_cast<const bf16x4*>(sp + (size_t)(mrow + k * RPI) * lds_ + ncol);
+        dst[k] = *reinterpret_cast<const bf16x4*>(sp + (size_t)(m0 + wm + i * 32 + rsub + k * RPI) * lds_ + ncol);
     }
+  };
+  side_request(0, side[0]);
 #pragma unroll
-    for (int ii = 0; ii < 2; ii++)
+  for (int i = 0; i < TM; i++) {
+    const int mrow = m0 + wm + i * 32 + rsub;
+    if (i + 1 < TM) side_request(i + 1, side[(i + 1) & 1]);
 #pragma unroll
-      for (int j = 0; j < TN; j++)
+    for (int j = 0; j < TN; j++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          const int row = ii * 32 + (lane & 31);
-          const int chunk = j * 8 + g * 2 + (lane >> 5);
-          const f32x16& t = acc[half * 2 + ii][j];
-          *reinterpret_cast<float4*>(wbuf + row * WC + ((chunk ^ (row & 7)) << 2)) =
-              make_float4(t[g * 4], t[g * 4 + 1], t[g * 4 + 2], t[g * 4 + 3]);
-        }
+      for (int g = 0; g < 4; g++) {
+        const int row = lane_e & 31;
+        const int chunk = j * 8 + g * 2 + (lane_e >> 5);
+        const f32x16& t = acc[i][j];
+        *reinterpret_cast<float4*>(wbuf + row * WC + ((chunk ^ (row & 7)) << 2)) =
+            make_float4(t[g * 4], t[g * 4 + 1], t[g * 4 + 2], t[g * 4 + 3]);
+      }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -450,7 +485,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
         if (ADD_C) {
           sd = old_c[u];
         } else if (SIDE) {
-          const bf16x4 v = side[k0 + u];
+          const bf16x4 v = side[i & 1][k0 + u];
           sd = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
         }
         mfma_epilogue4<EM>(e, mrow + (k0 + u) * RPI, ncol, a[u], bias, sd);
@@ -460,6 +495,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
+  }  // tile loop
+  lds_dma_wait();  // nothing is in flight here; stated for whoever reads the assembly in a straight line
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -502,7 +539,15 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
     configured = true;
   }
   const int tiles_m = g.M / BT, tiles_n = g.N / BT;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), lds, s, g.M, g.N, g.K, (const bf16_t*)g.A, g.lda,
+  static int n_cu = 0;  // benign race: same value from every thread
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    FAX_HIP(hipGetDevice(&dev));
+    FAX_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    n_cu = v > 0 ? v : 256;
+  }
+  const int grid = tiles_m * tiles_n < n_cu ? tiles_m * tiles_n : n_cu;  // persistent: one workgroup per CU
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.M, g.N, g.K, (const bf16_t*)g.A, g.lda,
                      (const bf16_t*)g.B, g.ldb, e, tiles_m, tiles_n);
   FAX_LAUNCH_CHECK("gemm_mfma");
   return FAX_OK;

@@ -35,6 +35,11 @@ GEMM_CASES = [
     ("bf16", fax.PATH_MFMA, 0, 1, 4096, 2048, 128),
     ("bf16", fax.PATH_MFMA, 1, 0, 2048, 4096, 192),
     ("bf16", fax.PATH_MFMA, 1, 1, 4096, 2048, 64),
+    # more 256-tiles than CUs and not a multiple of either 8 or the CU count: some workgroups of the
+    # persistent kernel do two tiles, some one; K of one, two and three slabs
+    ("bf16", fax.PATH_MFMA, 0, 0, 4352, 4352, 64),
+    ("bf16", fax.PATH_MFMA, 0, 1, 4352, 4352, 128),
+    ("bf16", fax.PATH_MFMA, 1, 0, 4352, 4352, 192),
 ]
 
 
