@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA tiles per wave in each direction
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // LDS: three buffers for A slabs, then two for B slabs (see the pipeline below).
-  constexpr int A_BUFS = 3, B_BUFS = 2;
+  constexpr int A_BUFS = 3;  // and two for B
   constexpr int B_BASE = A_BUFS * LA::BYTES;
 
   // Persistent workgroups: workgroup b works through tiles b, b + gridDim.x, ...  (the host

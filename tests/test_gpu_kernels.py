@@ -194,3 +194,31 @@ def test_adamw_three_steps_and_bf16_copy(n):
     md.zero_(); vd.zero_()
     fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), None, n, hp, 1)
     assert rel_max(to_np(pd), p0 * (1 - 1e-5) - 1e-3 * g / (np.abs(g) + 1e-8)) <= 1e-6
+
+
+# ------------------------------------------------------------------------- per-kernel timing
+def test_timing_report_names_kernels_and_counts_their_work():
+    """bench.py's roofline entry rests on this: HIP events around each kernel family on the launch stream."""
+    M, N, K = 512, 256, 128
+    A = to_dev(round_to_bf16(np.ones((M, K))), "bf16"); B = to_dev(round_to_bf16(np.ones((K, N))), "bf16")
+    Cd = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    fax.fax_timing_enable(1)
+    try:
+        for _ in range(3):
+            fax.fax_gemm(fax.FAX_BF16, 0, 0, M, N, K, A, K, B, N, Cd, N)
+        torch.cuda.synchronize()
+        rows = fax.fax_timing_report(64)
+    finally:
+        fax.fax_timing_enable(0)
+    gemm = [r for r in rows if r["name"].startswith("gemm_mfma_Ak_Bm")]
+    assert len(gemm) == 1, rows
+    assert gemm[0]["launches"] == 3 and gemm[0]["ms"] > 0.0
+    assert gemm[0]["work"] == pytest.approx(3 * 2.0 * M * N * K)
+    # switched off: nothing is recorded
+    fax.fax_gemm(fax.FAX_BF16, 0, 0, M, N, K, A, K, B, N, Cd, N)
+    torch.cuda.synchronize()
+    fax.fax_timing_enable(1)
+    try:
+        assert fax.fax_timing_report(64) == []
+    finally:
+        fax.fax_timing_enable(0)
