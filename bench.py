@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "t1_5120", "t1_10240", "t1_16384"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--graph", action="store_true",
@@ -59,6 +59,7 @@ def main():
     cfg = get_config(args.config)
     is_model = isinstance(cfg, ModelShape)
     sh = cfg.blk if is_model else cfg
+    tp_share = sh.H * sh.dh != sh.D  # one tensor-parallel rank's share: the un-reduced partial sums are outputs too
     td = torch.bfloat16
     code = fax.FAX_BF16
 
@@ -66,7 +67,7 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(dtype).contiguous()
 
     dims = fax.block_dims(sh.B, sh.S, sh.D, sh.H, sh.dh, sh.F, code, fax.FAX_GELU_TANH, sh.ln_eps,
-                          fax.FAX_FLAG_TP_PARTIAL if args.config == "cfg4" else 0)
+                          fax.FAX_FLAG_TP_PARTIAL if tp_share else 0)
     hp = fax.FaxAdamW(**ADAMW_DEFAULT)
     T = sh.T
 
@@ -109,8 +110,8 @@ def main():
         wsb = fax.fax_block_workspace_bytes(dims)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
         gd = [{k: torch.empty(t.shape, dtype=torch.float32, device=dev) for k, t in p.items()} for p in pd]
-        pa = torch.empty_like(dyd) if args.config == "cfg4" else None
-        pm = torch.empty_like(dyd) if args.config == "cfg4" else None
+        pa = torch.empty_like(dyd) if tp_share else None
+        pm = torch.empty_like(dyd) if tp_share else None
         with_adam = args.config == "cfg2"
         if with_adam:
             master = [{k: t.float().clone() for k, t in p.items()} for p in pd]
@@ -249,7 +250,7 @@ def cpu_baseline(name, cfg):
         toks = small.blk.T
         sample = "oracle loss+gradients of the same model cut to B=1, S=512, L=2, V=8192 (float64), one run"
     else:
-        S = min(cfg.S, 1024 if name == "cfg4" else 2048)
+        S = min(cfg.S, 2048 if cfg.D <= 4096 else 1024 if cfg.D <= 12288 else 512)
         small = cfg.scaled(B=1, S=S, L=1)
         p, x, dy = make_block_inputs(small, seed=0)
         t0 = time.perf_counter()

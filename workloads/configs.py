@@ -1,4 +1,4 @@
-"""Workload shapes: the five benchmark configurations plus scaled-down cousins.
+"""Workload shapes: the five benchmark configurations, the capacity-table shares, scaled-down cousins.
 
 B batch, S sequence length, D model width, H heads held locally, dh head
 width, F feed-forward width held locally, L layers, V vocabulary.  H*dh may
@@ -84,6 +84,13 @@ CONFIGS = {
     # GPT-style train step with a tied vocabulary of 51200
     "cfg5": ModelShape(BlockShape(B=8, S=2048, D=2048, H=16, dh=128, F=8192, dtype="bf16",
                                   sigma_w=0.02, L=12), V=51200, S_max=2048),
+    # One tensor-parallel rank's block at the operating point of the capacity table (Table 1):
+    # batch 1, sequence 2048, hidden 5120 / 10240 / 16384, "maximal tensor parallelism".  The
+    # paper does not say how many heads or which feed-forward width; taken here: 128-wide heads,
+    # F = 4 D, split 8 ways (one 8-GPU node as the model axis), biases and weight scale as cfg4.
+    "t1_5120": BlockShape(B=1, S=2048, D=5120, H=5, dh=128, F=2560, dtype="bf16", sigma_w=0.006, L=1),
+    "t1_10240": BlockShape(B=1, S=2048, D=10240, H=10, dh=128, F=5120, dtype="bf16", sigma_w=0.006, L=1),
+    "t1_16384": BlockShape(B=1, S=2048, D=16384, H=16, dh=128, F=8192, dtype="bf16", sigma_w=0.006, L=1),
 }
 
 ADAMW_DEFAULT = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.01)
