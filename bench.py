@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "t1_5120", "t1_10240", "t1_16384"])
+    ap.add_argument("--config", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "t1_5120", "t1_10240", "t1_16384", "fig4_124m"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--graph", action="store_true",
@@ -170,6 +170,9 @@ def main():
     torch.cuda.synchronize()
     rows = fax.fax_timing_report(64)
     fax.fax_timing_enable(0)
+    # fax_train_step also times its phases as wholes (forward / loss / backward / update, Fig. 4)
+    phases = {r["name"][6:] + "_ms": round(r["ms"] / args.steps, 4) for r in rows if r["name"].startswith("phase_")}
+    rows = [r for r in rows if not r["name"].startswith("phase_")]
     rows.sort(key=lambda r: -r["ms"])
     dom = rows[0]
     if dom["unit"] == 0:
@@ -212,7 +215,7 @@ def main():
         "model_tflops": round(tflops, 2), "mfma_peak_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "model_tflops_unhalved_attention": round(flops_full / dt / 1e12, 2),
         "model_flop_per_step": flops,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "phases": phases or None, "kernels": kernels,
     }
     print(json.dumps(out))
 

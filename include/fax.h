@@ -55,6 +55,7 @@ enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
 
 /* FaxModelDims.flags */
 #define FAX_FLAG_SKIP_UPDATE 1u /* fax_train_step: stop after the gradients */
+#define FAX_FLAG_ACCUMULATE 2u  /* fax_train_step: add this call's gradients to `grads` instead of overwriting */
 
 /* Shape of one decoder block as one device holds it.  H and F are the LOCAL
  * head count and feed-forward width; H*dh need not equal D (a tensor-parallel
@@ -117,6 +118,9 @@ typedef struct FaxModelDims {
   int32_t V;        /* vocabulary */
   int32_t S_max;    /* rows of the position table, >= blk.S */
   uint32_t flags;
+  int32_t micro_batches; /* 0 or 1: this call's batch is the whole step's.  n > 1: it is one of n equal
+                          * micro-batches of the step; its loss gradient is scaled by 1/n so that the
+                          * accumulated gradients are those of the mean loss over the whole batch. */
 } FaxModelDims;
 
 /* Pointer table of the model's parameters, or buffers shaped like them.
@@ -183,6 +187,9 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
  *   x0 = tok_emb[tokens] + pos_emb[s];  L blocks;  hf = LN(x_L; lnf);  logits = hf tok_emb^T;
  *   loss = mean over B*S positions of logsumexp(logits) - logits[label];
  *   gradients of every tensor; then fax_adamw_step on every tensor unless FAX_FLAG_SKIP_UPDATE.
+ * Gradient accumulation over micro-batches: call once per micro-batch with dims.micro_batches = n,
+ * FAX_FLAG_ACCUMULATE on every call but the first and FAX_FLAG_SKIP_UPDATE on every call but the last.
+ * loss_out is always the mean loss of the call's own batch.
  * params: compute copy in dims.blk.dtype (rewritten by the update when bf16).
  * master, m, v: fp32 state (for FAX_F32, master may equal params: one copy, updated in place).
  * grads: fp32, overwritten.  tokens, labels: int32 [B,S], values in [0,V) (caller validates).
@@ -192,6 +199,15 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
                    const FaxModelTensors* m, const FaxModelTensors* v, const FaxModelTensors* grads,
                    const int32_t* tokens, const int32_t* labels, const FaxAdamW* hp, int step,
                    float* loss_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The validation step, one of the functions the framework compiles besides the training step
+ * (Sec. 2.1): forward pass and mean loss as in fax_train_step, nothing kept for a backward pass,
+ * no gradient written.  Workspace: fax_eval_workspace_bytes() (activations of one layer, not L).
+ */
+int fax_eval_workspace_bytes(const FaxModelDims* dims, size_t* out);
+int fax_eval_step(const FaxModelDims* dims, const FaxModelTensors* params, const int32_t* tokens,
+                  const int32_t* labels, float* loss_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Building blocks, exported so each kernel can be checked and timed alone.

@@ -20,6 +20,7 @@ FAX_F32, FAX_BF16 = 0, 1
 FAX_GELU_TANH, FAX_GELU_ERF = 0, 1
 FAX_FLAG_TP_PARTIAL = 1
 FAX_FLAG_SKIP_UPDATE = 1
+FAX_FLAG_ACCUMULATE = 2
 PATH_AUTO, PATH_SCALAR, PATH_MFMA = 0, 1, 2
 
 TENSOR_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -56,7 +57,7 @@ class FaxAdamW(C.Structure):
 
 class FaxModelDims(C.Structure):
     _fields_ = [("blk", FaxBlockDims), ("L", C.c_int32), ("V", C.c_int32), ("S_max", C.c_int32),
-                ("flags", C.c_uint32)]
+                ("flags", C.c_uint32), ("micro_batches", C.c_int32)]
 
 
 class FaxModelTensors(C.Structure):
@@ -84,6 +85,8 @@ def _load():
         "fax_block_bwd_layout": (i32, [P(FaxBlockDims), P(FaxBwdLayout)]),
         "fax_block_workspace_bytes": (i32, [P(FaxBlockDims), P(sz)]),
         "fax_train_workspace_bytes": (i32, [P(FaxModelDims), P(sz)]),
+        "fax_eval_workspace_bytes": (i32, [P(FaxModelDims), P(sz)]),
+        "fax_eval_step": (i32, [P(FaxModelDims), P(FaxModelTensors), vp, vp, vp, vp, sz, vp]),
         "fax_block_fwd": (i32, [P(FaxBlockDims), P(FaxBlockTensors), vp, vp, vp, vp, vp, vp, sz, vp]),
         "fax_block_bwd": (i32, [P(FaxBlockDims), P(FaxBlockTensors), vp, vp, vp, vp, P(FaxBlockTensors), i32,
                                 vp, sz, vp]),
@@ -194,6 +197,18 @@ def fax_train_workspace_bytes(mdims):
     out = C.c_size_t()
     _check(_lib.fax_train_workspace_bytes(C.byref(mdims), C.byref(out)))
     return out.value
+
+
+def fax_eval_workspace_bytes(mdims):
+    out = C.c_size_t()
+    _check(_lib.fax_eval_workspace_bytes(C.byref(mdims), C.byref(out)))
+    return out.value
+
+
+def fax_eval_step(mdims, params, tokens, labels, loss_out, ws, ws_bytes, stream=None):
+    tab = model_tensors(params)
+    _check(_lib.fax_eval_step(C.byref(mdims), C.byref(tab.struct) if tab is not None else None, _ptr(tokens), _ptr(labels), _ptr(loss_out), _ptr(ws),
+                              ws_bytes, _stream(stream)))
 
 
 def fax_block_fwd(dims, params, x, y, saved, p_attn=None, p_mlp=None, ws=None, ws_bytes=0, stream=None):

@@ -479,6 +479,74 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
   return adamw((float*)master, (float*)m, (float*)v, (const float*)grad, lowp, n, *hp, step, (hipStream_t)stream);
 }
 
+// Evaluation: two activation buffers that take turns, one block's worth of saved tensors that every
+// layer overwrites, the final LayerNorm, the logits, per-row losses.
+struct EvalWs {
+  size_t x[2], saved, hf, muf, rstdf, logits, row_loss, total;
+};
+
+static void eval_layout(const FaxModelDims& m, EvalWs* W) {
+  const FaxBlockDims& d = m.blk;
+  Sizes z(d);
+  FaxSavedLayout L;
+  saved_layout(d, &L);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o += align_up(bytes); return r; };
+  W->x[0] = take(z.T * z.D * z.es);
+  W->x[1] = take(z.T * z.D * z.es);
+  W->saved = take(L.total);
+  W->hf = take(z.T * z.D * z.es);
+  W->muf = take(z.T * 4);
+  W->rstdf = take(z.T * 4);
+  W->logits = take(z.T * (size_t)m.V * z.es);
+  W->row_loss = take(z.T * 4);
+  W->total = o;
+}
+
+int fax_eval_workspace_bytes(const FaxModelDims* dims, size_t* out) {
+  size_t train = 0;
+  FAX_TRY(fax_train_workspace_bytes(dims, &train));  // same validation of dims
+  EvalWs W;
+  eval_layout(*dims, &W);
+  *out = W.total;
+  return FAX_OK;
+}
+
+int fax_eval_step(const FaxModelDims* dims, const FaxModelTensors* params, const int32_t* tokens, const int32_t* labels,
+                  float* loss_out, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  FAX_TRY(fax_eval_workspace_bytes(dims, &need));
+  FAX_TRY(check_model_tensors(params, dims->L, "params"));
+  FAX_TRY(check_ptr(tokens, "tokens"));
+  FAX_TRY(check_ptr(labels, "labels"));
+  FAX_TRY(check_ptr(loss_out, "loss_out"));
+  FAX_TRY(check_ptr(ws, "ws"));
+  if (ws_bytes < need) {
+    set_error("workspace of %zu bytes is smaller than the %zu required", ws_bytes, need);
+    return FAX_ERR_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  const FaxBlockDims& d = dims->blk;
+  EvalWs W;
+  eval_layout(*dims, &W);
+  Sizes z(d);
+  char* w = (char*)ws;
+  const int T = (int)z.T, D = d.D, V = dims->V;
+  FaxBlockDims bd = d;
+  bd.flags &= ~FAX_FLAG_TP_PARTIAL;
+  FAX_TRY(embed_fwd(d.dtype, d.B, d.S, D, tokens, params->tok_emb, params->pos_emb, w + W.x[0], s));
+  for (int l = 0; l < dims->L; l++)
+    FAX_TRY(block_fwd_impl(bd, params->blocks[l], w + W.x[l & 1], w + W.x[(l + 1) & 1], w + W.saved, nullptr, nullptr, s));
+  FAX_TRY(ln_fwd(d.dtype, T, D, w + W.x[dims->L & 1], params->lnf_g, params->lnf_b, d.ln_eps, w + W.hf,
+                 (float*)(w + W.muf), (float*)(w + W.rstdf), s));
+  GemmArgs g;  // logits = hf E^T
+  g.dtype = d.dtype; g.ta = false; g.tb = true;
+  g.M = T; g.N = V; g.K = D;
+  g.A = w + W.hf; g.lda = D; g.B = params->tok_emb; g.ldb = D; g.C = w + W.logits; g.ldc = V;
+  FAX_TRY(gemm(g, s));
+  return cross_entropy(d.dtype, T, V, w + W.logits, labels, nullptr, (float*)(w + W.row_loss), loss_out, 1.0f, s);
+}
+
 int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, const FaxModelTensors* master,
                    const FaxModelTensors* m, const FaxModelTensors* v, const FaxModelTensors* grads,
                    const int32_t* tokens, const int32_t* labels, const FaxAdamW* hp, int step, float* loss_out, void* ws,
@@ -487,6 +555,9 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   FAX_TRY(fax_train_workspace_bytes(dims, &need));
   const FaxBlockDims& d = dims->blk;
   const bool update = !(dims->flags & FAX_FLAG_SKIP_UPDATE);
+  const bool acc = (dims->flags & FAX_FLAG_ACCUMULATE) != 0;
+  if (dims->micro_batches < 0) { set_error("micro_batches must be >= 0, got %d", dims->micro_batches); return FAX_ERR_INVALID_ARG; }
+  const float grad_scale = dims->micro_batches > 1 ? 1.0f / (float)dims->micro_batches : 1.0f;
   FAX_TRY(check_model_tensors(params, dims->L, "params"));
   FAX_TRY(check_model_tensors(grads, dims->L, "grads"));
   if (update) {
@@ -523,12 +594,18 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   FaxBlockDims bd = d;
   bd.flags &= ~FAX_FLAG_TP_PARTIAL;
 
+  // The three phases the paper times separately (Fig. 4), then the update; with fax_timing_enable
+  // each gets a record of its own ("phase_*") around the per-kernel ones.
+  const double fwd_flop = (double)L * (2.0 * T * (3.0 * D * z.Hd + (double)z.Hd * D + 2.0 * D * d.F) +
+                                       2.0 * d.B * d.H * (double)d.S * d.S * d.dh) + 2.0 * T * (double)D * V;
+  const char* xL = w + W.xs + W.x_stride * L;
   // forward
+  {
+  Timed phase_("phase_forward", WORK_FLOP, fwd_flop, s);
   FAX_TRY(embed_fwd(d.dtype, d.B, d.S, D, tokens, params->tok_emb, params->pos_emb, w + W.xs, s));
   for (int l = 0; l < L; l++)
     FAX_TRY(block_fwd_impl(bd, params->blocks[l], w + W.xs + W.x_stride * l, w + W.xs + W.x_stride * (l + 1),
                            w + W.saved + W.saved_stride * l, nullptr, nullptr, s));
-  const char* xL = w + W.xs + W.x_stride * L;
   FAX_TRY(ln_fwd(d.dtype, T, D, xL, params->lnf_g, params->lnf_b, d.ln_eps, w + W.hf, (float*)(w + W.muf),
                  (float*)(w + W.rstdf), s));
   GemmArgs g;  // logits = hf E^T
@@ -536,26 +613,36 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   g.M = T; g.N = V; g.K = D;
   g.A = w + W.hf; g.lda = D; g.B = params->tok_emb; g.ldb = D; g.C = w + W.logits; g.ldc = V;
   FAX_TRY(gemm(g, s));
+  }
   // loss and its gradient, in place over the logits
-  FAX_TRY(cross_entropy(d.dtype, T, V, w + W.logits, labels, w + W.logits, (float*)(w + W.row_loss), loss_out, s));
+  {
+  Timed phase_("phase_loss", WORK_BYTE, 2.0 * T * (double)V * z.es, s);
+  FAX_TRY(cross_entropy(d.dtype, T, V, w + W.logits, labels, w + W.logits, (float*)(w + W.row_loss), loss_out, grad_scale,
+                        s));
+  }
+  {
+  Timed phase_("phase_backward", WORK_FLOP, 2.0 * fwd_flop, s);
   // output projection backward: dE = dlogits^T hf ; dhf = dlogits E
-  g = GemmArgs(); g.dtype = d.dtype; g.ta = true; g.tb = false;
+  GemmArgs g; g.dtype = d.dtype; g.ta = true; g.tb = false;
   g.M = V; g.N = D; g.K = T;
   g.A = w + W.logits; g.lda = V; g.B = w + W.hf; g.ldb = D; g.C = grads->tok_emb; g.ldc = D; g.c_f32 = true;
+  g.accumulate = acc;
   FAX_TRY(gemm(g, s));
   g = GemmArgs(); g.dtype = d.dtype;
   g.M = T; g.N = D; g.K = V;
   g.A = w + W.logits; g.lda = V; g.B = params->tok_emb; g.ldb = D; g.C = w + W.dhf; g.ldc = D;
   FAX_TRY(gemm(g, s));
   FAX_TRY(ln_bwd(d.dtype, T, D, w + W.dhf, xL, (const float*)(w + W.muf), (const float*)(w + W.rstdf), params->lnf_g,
-                 nullptr, w + W.dcur, (float*)grads->lnf_g, (float*)grads->lnf_b, false, w + W.blk, s));
+                 nullptr, w + W.dcur, (float*)grads->lnf_g, (float*)grads->lnf_b, acc, w + W.blk, s));
   for (int l = L - 1; l >= 0; l--)
     FAX_TRY(block_bwd_impl(bd, params->blocks[l], w + W.xs + W.x_stride * l, w + W.dcur,
-                           w + W.saved + W.saved_stride * l, w + W.dcur, grads->blocks[l], false, w + W.blk, s));
+                           w + W.saved + W.saved_stride * l, w + W.dcur, grads->blocks[l], acc, w + W.blk, s));
   // embedding backward: token rows add onto the output projection's share; positions beyond S get zero
-  FAX_TRY(fill_zero(grads->pos_emb, (size_t)dims->S_max * D * 4, s));
-  FAX_TRY(embed_bwd(d.dtype, d.B, d.S, D, tokens, w + W.dcur, (float*)grads->tok_emb, (float*)grads->pos_emb, s));
+  if (!acc) FAX_TRY(fill_zero(grads->pos_emb, (size_t)dims->S_max * D * 4, s));
+  FAX_TRY(embed_bwd(d.dtype, d.B, d.S, D, tokens, w + W.dcur, (float*)grads->tok_emb, (float*)grads->pos_emb, acc, s));
+  }
   if (!update) return FAX_OK;
+  Timed phase_("phase_update", WORK_BYTE, 28.0 * ((double)V * D + (double)dims->S_max * D), s);
 
   const bool lowp = d.dtype == FAX_BF16;
   auto upd = [&](void* P, void* Mst, void* Mo, void* Vo, const void* G, size_t n) {
@@ -676,7 +763,7 @@ int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t
   if (N <= 0 || V <= 0) { set_error("bad cross-entropy size N=%d V=%d", N, V); return FAX_ERR_INVALID_ARG; }
   FAX_TRY(check_ptr(logits, "logits")); FAX_TRY(check_ptr(labels, "labels")); FAX_TRY(check_ptr(dlogits, "dlogits"));
   FAX_TRY(check_ptr(row_loss, "row_loss")); FAX_TRY(check_ptr(loss_out, "loss_out"));
-  return cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, (hipStream_t)stream);
+  return cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, 1.0f, (hipStream_t)stream);
 }
 
 }  // extern "C"

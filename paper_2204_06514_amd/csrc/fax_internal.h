@@ -87,13 +87,14 @@ int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx,
                   const void* dctx, void* dqkv, float* delta, hipStream_t s);
 
 // ---- loss, embedding, optimizer ---------------------------------------------------------------
+// dlogits = grad_scale (softmax - onehot) / N, may alias logits, NULL for the loss alone
 int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
-                  float* row_loss, float* loss_out, hipStream_t s);
+                  float* row_loss, float* loss_out, float grad_scale, hipStream_t s);
 int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb,
               void* x0, hipStream_t s);
-// g_tok[tokens[b,s]] += dx0[b,s] (fp32 atomics); g_pos[s] = sum_b dx0[b,s]; rows of g_pos beyond S untouched.
+// g_tok[tokens[b,s]] += dx0[b,s] (fp32 atomics); g_pos[s] (+)= sum_b dx0[b,s]; rows of g_pos beyond S untouched.
 int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
-              hipStream_t s);
+              bool accumulate_pos, hipStream_t s);
 int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
           hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -7,7 +7,8 @@ namespace fax {
 // ---------------------------------------------------------------------------------------------
 // Cross-entropy.  One 1024-thread block per row; the row is read from HBM once (cached in
 // registers as raw 16-byte vectors when it fits), reduced to max and sum-exp, and the gradient
-// (softmax - onehot)/N is written over it.
+// grad_scale (softmax - onehot)/N is written over it (or anywhere else; nowhere when dlogits is NULL:
+// loss only).
 // ---------------------------------------------------------------------------------------------
 static constexpr int CE_THREADS = 1024;
 static constexpr int CE_MAXV = 8;
@@ -26,7 +27,7 @@ __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) 
 template <typename T, bool CACHED>
 __global__ __launch_bounds__(CE_THREADS) void ce_kernel(int N, int V, const T* __restrict__ logits,
                                                         const int32_t* __restrict__ labels, T* __restrict__ dlogits,
-                                                        float* __restrict__ row_loss) {
+                                                        float* __restrict__ row_loss, float grad_scale) {
   using Vv = Vec16<T>;
   __shared__ float red[CE_THREADS / 64];
   const int row = blockIdx.x;
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(int N, int V, const T* _
   T* dz = dlogits + (size_t)row * V;
   const int nvec = V / Vv::N;  // CACHED requires V % Vv::N == 0
   const int label = labels[row];
-  const float invN = 1.f / (float)N;
+  const float invN = grad_scale / (float)N;
   Vv zv[CE_MAXV];
   float mx = -INFINITY;
   if (CACHED) {
@@ -67,6 +68,7 @@ __global__ __launch_bounds__(CE_THREADS) void ce_kernel(int N, int V, const T* _
   se = block_reduce(se, red, false);
   const float inv = invN / se;
   if (threadIdx.x == 0) row_loss[row] = (mx + logf(se)) - to_f(z[label]);
+  if (!dlogits) return;
   __syncthreads();  // z[label] is read before anyone overwrites it (dz may alias z)
   if (CACHED) {
 #pragma unroll
@@ -103,12 +105,14 @@ __global__ __launch_bounds__(1024) void mean_kernel(int N, const float* __restri
 
 template <typename T>
 static int ce_t(int N, int V, const T* logits, const int32_t* labels, T* dlogits, float* row_loss, float* loss_out,
-                hipStream_t s) {
+                float grad_scale, hipStream_t s) {
   constexpr int VN = Vec16<T>::N;
   if (V % VN == 0 && V / VN <= CE_THREADS * CE_MAXV)
-    hipLaunchKernelGGL((ce_kernel<T, true>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss);
+    hipLaunchKernelGGL((ce_kernel<T, true>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss,
+                       grad_scale);
   else
-    hipLaunchKernelGGL((ce_kernel<T, false>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss);
+    hipLaunchKernelGGL((ce_kernel<T, false>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss,
+                       grad_scale);
   FAX_LAUNCH_CHECK("cross_entropy");
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, s, N, row_loss, loss_out);
   FAX_LAUNCH_CHECK("cross_entropy_mean");
@@ -116,11 +120,12 @@ static int ce_t(int N, int V, const T* logits, const int32_t* labels, T* dlogits
 }
 
 int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits, float* row_loss,
-                  float* loss_out, hipStream_t s) {
+                  float* loss_out, float grad_scale, hipStream_t s) {
   if (N == 0) return FAX_OK;
-  Timed t_("cross_entropy", WORK_BYTE, 2.0 * N * V * (dtype == FAX_F32 ? 4.0 : 2.0), s);
-  if (dtype == FAX_F32) return ce_t<float>(N, V, (const float*)logits, labels, (float*)dlogits, row_loss, loss_out, s);
-  return ce_t<bf16_t>(N, V, (const bf16_t*)logits, labels, (bf16_t*)dlogits, row_loss, loss_out, s);
+  Timed t_("cross_entropy", WORK_BYTE, (dlogits ? 2.0 : 1.0) * N * V * (dtype == FAX_F32 ? 4.0 : 2.0), s);
+  if (dtype == FAX_F32)
+    return ce_t<float>(N, V, (const float*)logits, labels, (float*)dlogits, row_loss, loss_out, grad_scale, s);
+  return ce_t<bf16_t>(N, V, (const bf16_t*)logits, labels, (bf16_t*)dlogits, row_loss, loss_out, grad_scale, s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -149,10 +154,10 @@ __global__ __launch_bounds__(256) void embed_bwd_tok_kernel(int D, const int32_t
 
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_pos_kernel(int B, int S, int D, const T* __restrict__ dx0,
-                                                            float* __restrict__ g_pos) {
+                                                            float* __restrict__ g_pos, int accumulate) {
   const int s = blockIdx.x;
   for (int d = threadIdx.x; d < D; d += 256) {
-    float a = 0.f;
+    float a = accumulate ? g_pos[(size_t)s * D + d] : 0.f;
     for (int b = 0; b < B; b++) a += to_f(dx0[((size_t)b * S + s) * D + d]);
     g_pos[(size_t)s * D + d] = a;
   }
@@ -173,15 +178,17 @@ int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void*
 }
 
 int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
-              hipStream_t s) {
+              bool accumulate_pos, hipStream_t s) {
   if (B * S == 0) return FAX_OK;
   Timed t_("embed_bwd", WORK_BYTE, 2.0 * B * S * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * B * S * D + 4.0 * S * D, s);
   if (dtype == FAX_F32) {
     hipLaunchKernelGGL((embed_bwd_tok_kernel<float>), dim3(B * S), dim3(256), 0, s, D, tokens, (const float*)dx0, g_tok);
-    hipLaunchKernelGGL((embed_bwd_pos_kernel<float>), dim3(S), dim3(256), 0, s, B, S, D, (const float*)dx0, g_pos);
+    hipLaunchKernelGGL((embed_bwd_pos_kernel<float>), dim3(S), dim3(256), 0, s, B, S, D, (const float*)dx0, g_pos,
+                       accumulate_pos ? 1 : 0);
   } else {
     hipLaunchKernelGGL((embed_bwd_tok_kernel<bf16_t>), dim3(B * S), dim3(256), 0, s, D, tokens, (const bf16_t*)dx0, g_tok);
-    hipLaunchKernelGGL((embed_bwd_pos_kernel<bf16_t>), dim3(S), dim3(256), 0, s, B, S, D, (const bf16_t*)dx0, g_pos);
+    hipLaunchKernelGGL((embed_bwd_pos_kernel<bf16_t>), dim3(S), dim3(256), 0, s, B, S, D, (const bf16_t*)dx0, g_pos,
+                       accumulate_pos ? 1 : 0);
   }
   FAX_LAUNCH_CHECK("embed_bwd");
   return FAX_OK;

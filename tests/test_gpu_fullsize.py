@@ -198,3 +198,47 @@ def test_capacity_table_share_16384():
         assert np.isfinite(big[k]).all(), k
     for k in PARAM_NAMES:
         assert np.isfinite(big["grads"][k]).all() and np.abs(big["grads"][k]).max() > 0, k
+
+
+# ---- the model of the per-phase timing figure (Fig. 4): 124M parameters, batch 32, sequence 2048 ----
+def test_fig4_model_reduced_depth_and_batch_full_vocabulary():
+    """Width 768, 12 heads of 64, vocabulary 50304, sequence 2048, at 2 layers and one batch row:
+    loss and every gradient against the oracle."""
+    ms = get_config("fig4_124m").scaled(B=1, L=2)
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=0)
+    loss_ref, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh)
+    loss, params, master, m, v, grads = run_train_step(ms, p, tok, lab, update=False)
+    assert abs(loss - loss_ref) <= 2e-3 * abs(loss_ref), (loss, loss_ref)
+    rep = {name: rel_fro(to_np(get(grads)), get(g_ref)) for name, get in _walk(grads)}
+    _assert_all(rep)
+
+
+def test_fig4_model_full_size_step_properties_and_phase_times():
+    """All 12 layers at batch 32: what must hold at any size (see the cfg5 test), and the timing
+    records of the three phases the paper's figure splits the step into."""
+    ms = get_config("fig4_124m")
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=0)
+    fax.fax_timing_enable(1)
+    try:
+        loss, params, master, m, v, grads = run_train_step(ms, p, tok, lab, update=True)
+        rows = {r["name"]: r for r in fax.fax_timing_report(64)}
+    finally:
+        fax.fax_timing_enable(0)
+    assert math.log(ms.V) - 0.05 <= loss <= math.log(ms.V) + 0.5, loss
+    hp = ADAMW_DEFAULT
+    for name, get in _walk(grads):
+        gt = get(grads)
+        assert torch.isfinite(gt).all(), name
+        ref = torch.from_numpy(np.ascontiguousarray(get(p), dtype=np.float32)).to(DEV)
+        step = (get(master) - ref).abs()
+        bound = hp["lr"] * (1.0 + hp["wd"] * ref.abs()) * 1.001 + 1e-7
+        assert bool((step <= bound).all()), name
+        assert torch.equal(get(params), get(master).to(torch.bfloat16)), name
+        if not name.endswith(("bqkv",)) and "pos_emb" not in name:
+            assert float(gt.abs().max()) > 0, name
+    for ph in ("phase_forward", "phase_loss", "phase_backward", "phase_update"):
+        assert rows[ph]["launches"] == 1 and rows[ph]["ms"] > 0, ph
+    # backward does twice the matrix work of forward; it cannot be faster, nor (here) four times slower
+    assert 1.0 <= rows["phase_backward"]["ms"] / rows["phase_forward"]["ms"] <= 4.0

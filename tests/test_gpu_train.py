@@ -110,3 +110,82 @@ def test_train_step_pos_rows_beyond_sequence_get_zero_gradient():
     _, _, _, _, _, grads = run_train_step(ms, p, tok, lab, update=False)
     assert torch.all(grads["pos_emb"][ms.blk.S:] == 0)
     assert torch.any(grads["pos_emb"][:ms.blk.S] != 0)
+
+
+# ---- the validation step and gradient accumulation over micro-batches -------------------------------
+@pytest.mark.parametrize("ms", CASES, ids=lambda m: "%s_D%d_V%d" % (m.blk.dtype, m.blk.D, m.V))
+def test_eval_step_gives_the_forward_loss_and_touches_nothing(ms):
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=3, generic=True)
+    logits, _ = orc.model_fwd(p, tok, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    loss_ref, _ = orc.cross_entropy(logits.reshape(-1, ms.V), lab.reshape(-1))
+    md = fax.FaxModelDims(dims_of(sh), sh.L, ms.V, ms.S_max, 0)
+    params = _dev_params(p, sh.dtype)
+    wsb = fax.fax_eval_workspace_bytes(md)
+    assert wsb < fax.fax_train_workspace_bytes(md)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    loss = torch.zeros(4, device=DEV)
+    fax.fax_eval_step(md, params, torch.from_numpy(tok).to(DEV), torch.from_numpy(lab).to(DEV), loss, ws, wsb)
+    torch.cuda.synchronize()
+    assert abs(loss[0].item() - loss_ref) <= (1e-5 if sh.dtype == "f32" else 2e-3) * abs(loss_ref)
+    for name, get in _walk(params):
+        assert np.array_equal(to_np(get(params)), get(p)), name
+    # the training step reports the same number
+    loss_t, *_ = run_train_step(ms, p, tok, lab, update=False)
+    assert abs(loss[0].item() - loss_t) <= 1e-6 * abs(loss_t)
+    with pytest.raises(fax.FaxError):
+        fax.fax_eval_step(md, params, torch.from_numpy(tok).to(DEV), torch.from_numpy(lab).to(DEV), loss, ws, wsb - 1)
+
+
+@pytest.mark.parametrize("ms", CASES[:2], ids=lambda m: "%s_D%d_V%d" % (m.blk.dtype, m.blk.D, m.V))
+def test_two_micro_batches_accumulate_to_the_full_batch_step(ms):
+    """Batch rows 0 and 1 as two calls (micro_batches = 2; the second adds to the gradients and applies
+    the update) against the oracle's gradients and AdamW step for the batch of two."""
+    sh = ms.blk
+    assert sh.B == 2
+    p, tok, lab = make_model_inputs(ms, seed=3, generic=True)
+    loss_ref, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    half = ms.scaled(B=1)
+    params = _dev_params(p, sh.dtype)
+    master = params if sh.dtype == "f32" else _like(params, src=params)
+    m = _like(params, 0.0); v = _like(params, 0.0); grads = _like(params, 7.0)
+    hp = fax.FaxAdamW(**ADAMW_DEFAULT)
+    loss = torch.zeros(4, device=DEV)
+    losses = []
+    for i, flags in enumerate((fax.FAX_FLAG_SKIP_UPDATE, fax.FAX_FLAG_ACCUMULATE | fax.FAX_FLAG_SKIP_UPDATE)):
+        md = fax.FaxModelDims(dims_of(half.blk), sh.L, ms.V, ms.S_max, flags, 2)
+        wsb = fax.fax_train_workspace_bytes(md)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+        fax.fax_train_step(md, params, master, m, v, grads, torch.from_numpy(tok[i:i + 1].copy()).to(DEV),
+                           torch.from_numpy(lab[i:i + 1].copy()).to(DEV), hp, 1, loss, ws, wsb)
+        torch.cuda.synchronize()
+        losses.append(loss[0].item())
+    assert abs(0.5 * (losses[0] + losses[1]) - loss_ref) <= (1e-5 if sh.dtype == "f32" else 2e-3) * abs(loss_ref)
+    t = tol(sh.dtype)
+    bad = {}
+    for name, get in _walk(grads):
+        e = err(to_np(get(grads)), get(g_ref), sh.dtype)
+        if not e <= t:
+            bad[name] = e
+    assert not bad, bad
+    # the same two calls on a fresh state, the second one now also applying the update
+    params = _dev_params(p, sh.dtype)
+    master = params if sh.dtype == "f32" else _like(params, src=params)
+    m = _like(params, 0.0); v = _like(params, 0.0); grads = _like(params, 7.0)
+    for i, flags in enumerate((fax.FAX_FLAG_SKIP_UPDATE, fax.FAX_FLAG_ACCUMULATE)):
+        md = fax.FaxModelDims(dims_of(half.blk), sh.L, ms.V, ms.S_max, flags, 2)
+        fax.fax_train_step(md, params, master, m, v, grads, torch.from_numpy(tok[i:i + 1].copy()).to(DEV),
+                           torch.from_numpy(lab[i:i + 1].copy()).to(DEV), hp, 1, loss, ws, wsb)
+    torch.cuda.synchronize()
+    a = ADAMW_DEFAULT
+    Hd = sh.Hd
+    bad = {}
+    for name, get in _walk(master):
+        ref, _, _ = orc.adamw(get(p), 0.0, 0.0, get(g_ref), a["lr"], a["beta1"], a["beta2"], a["eps"], a["wd"], 1)
+        got = to_np(get(master))
+        if name.endswith("bqkv"):
+            ref = np.concatenate([ref[:Hd], ref[2 * Hd:]]); got = np.concatenate([got[:Hd], got[2 * Hd:]])
+        e = np.abs(got - ref).max()
+        if not e <= 2.5 * a["lr"] * (1e-3 if sh.dtype == "f32" else 1.0):
+            bad[name] = e
+    assert not bad, bad

@@ -90,6 +90,12 @@ def test_adamw_and_train_argument_checks():
         fax.fax_train_workspace_bytes(md)
     md = fax.FaxModelDims(_dims(), 2, 100, 64, 0)
     assert fax.fax_train_workspace_bytes(md) > 0
+    # the validation step keeps one layer's activations, not L: smaller workspace, same dims checks
+    assert 0 < fax.fax_eval_workspace_bytes(md) < fax.fax_train_workspace_bytes(md)
+    with pytest.raises(fax.FaxError):
+        fax.fax_eval_workspace_bytes(fax.FaxModelDims(_dims(), 2, 100, 32, 0))
+    with pytest.raises(fax.FaxError):   # NULL parameter table is caught before anything is launched
+        fax.fax_eval_step(md, None, 4096, 4096, 4096, 4096, fax.fax_eval_workspace_bytes(md), stream=0)
 
 
 def test_gemm_argument_checks():

@@ -91,6 +91,11 @@ CONFIGS = {
     "t1_5120": BlockShape(B=1, S=2048, D=5120, H=5, dh=128, F=2560, dtype="bf16", sigma_w=0.006, L=1),
     "t1_10240": BlockShape(B=1, S=2048, D=10240, H=10, dh=128, F=5120, dtype="bf16", sigma_w=0.006, L=1),
     "t1_16384": BlockShape(B=1, S=2048, D=16384, H=16, dh=128, F=8192, dtype="bf16", sigma_w=0.006, L=1),
+    # The model of the per-phase timing figure (Fig. 4): "124M parameters", batch 32, sequence 2048.
+    # The paper gives the size only; taken here: 12 layers, D = 768, 12 heads of 64, F = 3072 and a
+    # vocabulary of 50304 (124.5M parameters with the position table), everything else as cfg5.
+    "fig4_124m": ModelShape(BlockShape(B=32, S=2048, D=768, H=12, dh=64, F=3072, dtype="bf16",
+                                       sigma_w=0.02, L=12), V=50304, S_max=2048),
 }
 
 ADAMW_DEFAULT = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.01)
