@@ -132,7 +132,7 @@ static void saved_layout(const FaxBlockDims& d, FaxSavedLayout* L) {
 
 struct BwdWs {
   FaxBwdLayout pub;
-  size_t delta, red, total;
+  size_t delta, red, splitk, total;
 };
 
 static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
@@ -152,6 +152,13 @@ static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
   size_t red = ln_bwd_ws_bytes(d.D);
   if (colsum_ws_bytes((int)widest) > red) red = colsum_ws_bytes((int)widest);
   W->red = take(red);
+  // scratch for the weight-gradient products whose contraction gets split (narrow models)
+  const int T = (int)z.T, D = (int)z.D, Hd = (int)z.Hd, F = (int)z.F;
+  size_t sk = gemm_split_ws_bytes(F, D, T);
+  sk = std::max(sk, gemm_split_ws_bytes(D, F, T));
+  sk = std::max(sk, gemm_split_ws_bytes(Hd, D, T));
+  sk = std::max(sk, gemm_split_ws_bytes(D, 3 * Hd, T));
+  W->splitk = take(sk);
   W->total = o;
   W->pub.total = o;
 }
@@ -286,6 +293,7 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
     g.M = Kdim; g.N = Ndim; g.K = T;
     g.A = act; g.lda = lda; g.B = grad; g.ldb = ldb; g.C = out; g.ldc = Ndim; g.c_f32 = true; g.accumulate = acc;
     g.colsum = (float*)bias_grad; g.colsum_ws = red;
+    g.split_ws = W.splitk < W.total ? ws + W.splitk : nullptr;
     return gemm(g, s);
   };
   auto dgrad = [&](const void* grad, int lda, int Ndim, const void* w, int ldw, int Kdim, void* out) {

@@ -57,10 +57,18 @@ struct GemmArgs {
   // sums in a separate pass.
   float* colsum = nullptr;
   void* colsum_ws = nullptr;
+  // Scratch for splitting the contraction (fp32-output form only): gemm_split_ws_bytes(M, N, K)
+  // bytes, or NULL to forbid the split.
+  void* split_ws = nullptr;
 };
 int gemm(const GemmArgs& g, hipStream_t s);
 int gemm_simt(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
+// A weight-gradient product of a narrow model has few output tiles and a very long contraction
+// (K = all tokens): it is then cut into `gemm_split_count` equal K ranges, each a full set of
+// tiles writing its own fp32 partial product, summed afterwards in a fixed order.  1 = no split.
+int gemm_split_count(int M, int N, int K);
+size_t gemm_split_ws_bytes(int M, int N, int K);
 int gemm_mfma(const GemmArgs& g, hipStream_t s);
 
 // ---- LayerNorm, column sums ---------------------------------------------------------------
@@ -71,6 +79,8 @@ int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const floa
            const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta, bool accumulate,
            void* ws, hipStream_t s);
 size_t colsum_ws_bytes(int N);
+// out[i] (+)= sum_p partial[p * n + i], p < parts, in that order
+int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s);
 // out[n] (+)= sum over rows of a[r, n]; a in dtype with leading dimension lda.
 int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws,
            hipStream_t s);
@@ -211,6 +221,8 @@ struct EpiArgs {
   const void* U; int ldu;
   int epi, gelu_form, c_f32, accumulate;
   float* colsum;
+  int splits;           // K ranges (fp32-output form); range r writes to C + r * split_stride
+  size_t split_stride;  // in elements
 };
 
 template <typename T>

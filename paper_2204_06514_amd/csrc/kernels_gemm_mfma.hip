@@ -219,7 +219,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   auto dma_b_from = [&](const bf16_t* tile_base, int q, int k0, int buf) {
     lds_dma16(tile_base + k0 * b_kstride, b_lane_off[q], smem_addr + B_BASE + buf * LB::BYTES + (wave * NSB + q) * 1024);
   };
-  const int nk = K / GK;
+  // With the contraction split (fp32-output form) the work items are (K range, tile) pairs: item
+  // v is tile v % nt over slabs [r nk, (r + 1) nk), r = v / nt, and writes the partial product r.
+  const int splits = e.splits > 1 ? e.splits : 1;
+  const int nk = K / GK / splits;
   // A tile starts with slab 0 in A[0], B[0] and slab 1 in A[1], B[1].  Everything but B of slab 1
   // can be requested while the previous tile's epilogue still uses A[2] and B[1].
   auto request_first_slabs = [&](const bf16_t* a_base, const bf16_t* b_base) {
@@ -234,12 +237,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   };
 
   int tm_i, tn_i;
-  tile_of(blockIdx.x, tm_i, tn_i);
-  request_first_slabs(a_tile_of(tm_i), b_tile_of(tn_i));
-  for (int tile = blockIdx.x; tile < nt; tile += gridDim.x) {
+  tile_of(blockIdx.x % nt, tm_i, tn_i);
+  size_t k_begin = (size_t)(blockIdx.x / nt) * nk * GK;
+  request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride);
+  for (int tile = blockIdx.x; tile < nt * splits; tile += gridDim.x) {
   const int m0 = tm_i * BM, n0 = tn_i * BN;
-  const bf16_t* const a_tile = a_tile_of(tm_i);
-  const bf16_t* const b_tile = b_tile_of(tn_i);
+  const bf16_t* const a_tile = a_tile_of(tm_i) + k_begin * a_kstride;
+  const bf16_t* const b_tile = b_tile_of(tn_i) + k_begin * b_kstride;
+  EpiArgs et = e;  // this item's view of the epilogue operands
+  if (em_kind(EM) == EK_F32) et.C = (float*)e.C + (size_t)(tile / nt) * e.split_stride;
   auto dma_a = [&](int q, int k0, int buf) { dma_a_from(a_tile, q, k0, buf); };
   auto dma_b = [&](int q, int k0, int buf) { dma_b_from(b_tile, q, k0, buf); };
   lds_dma_wait();   // slab 0 and A of slab 1 (requested a whole epilogue ago, except for the first tile)
@@ -424,9 +430,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     }
   }
   // the next tile's first slabs, before anything else of the epilogue
-  if (tile + (int)gridDim.x < nt) {
-    tile_of(tile + gridDim.x, tm_i, tn_i);
-    request_first_slabs(a_tile_of(tm_i), b_tile_of(tn_i));
+  if (tile + (int)gridDim.x < nt * splits) {
+    const int next = tile + gridDim.x;
+    tile_of(next % nt, tm_i, tn_i);
+    k_begin = (size_t)(next / nt) * nk * GK;
+    request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride);
   }
   // (lane index through an opaque copy: otherwise everything derived from it below is hoisted out of
   // the tile loop and kept in registers across the main loop, which has none to spare)
@@ -477,7 +485,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
       for (int u = 0; u < BATCH; u++) {
         const int row = (k0 + u) * RPI + rsub;
         a[u] = *reinterpret_cast<const float4*>(wbuf + row * WC + (((c4 >> 2) ^ (row & 7)) << 2));
-        if (ADD_C) old_c[u] = *reinterpret_cast<const float4*>((const float*)e.C + (size_t)(mrow + (k0 + u) * RPI) * e.ldc + ncol);
+        if (ADD_C) old_c[u] = *reinterpret_cast<const float4*>((const float*)et.C + (size_t)(mrow + (k0 + u) * RPI) * e.ldc + ncol);
       }
 #pragma unroll
       for (int u = 0; u < BATCH; u++) {
@@ -488,7 +496,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
           const bf16x4 v = side[i & 1][k0 + u];
           sd = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
         }
-        mfma_epilogue4<EM>(e, mrow + (k0 + u) * RPI, ncol, a[u], bias, sd);
+        mfma_epilogue4<EM>(et, mrow + (k0 + u) * RPI, ncol, a[u], bias, sd);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -501,11 +509,32 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-static int pick_tile(const GemmArgs& g) {
-  if (g.M % 256 == 0 && g.N % 256 == 0 && (size_t)(g.M / 256) * (g.N / 256) >= 128) return 256;
-  if (g.M % 128 == 0 && g.N % 128 == 0) return 128;
+// Both heuristics are written for the 256 CUs of the MI355X (no device query: workspace sizes are
+// computed on hosts without a GPU too).
+static constexpr int kCUs = 256;
+
+static int pick_tile_mn(int M, int N) {
+  if (M % 256 == 0 && N % 256 == 0 && (size_t)(M / 256) * (N / 256) >= 128) return 256;
+  if (M % 128 == 0 && N % 128 == 0) return 128;
   return 0;
 }
+
+int gemm_split_count(int M, int N, int K) {
+  const int bt = pick_tile_mn(M, N);
+  if (bt == 0 || K % GK) return 1;
+  const int tiles = (M / bt) * (N / bt), nk = K / GK;
+  if (2 * tiles > kCUs) return 1;  // at least half the CUs busy already
+  int s = 1;
+  while (2 * s * tiles <= kCUs && s < 16 && nk % (2 * s) == 0 && nk / (2 * s) >= 8) s *= 2;
+  return s;
+}
+
+size_t gemm_split_ws_bytes(int M, int N, int K) {
+  const int s = gemm_split_count(M, N, K);
+  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+}
+
+static int pick_tile(const GemmArgs& g) { return pick_tile_mn(g.M, g.N); }
 
 bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.dtype != FAX_BF16) return false;
@@ -546,7 +575,8 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
     FAX_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
     n_cu = v > 0 ? v : 256;
   }
-  const int grid = tiles_m * tiles_n < n_cu ? tiles_m * tiles_n : n_cu;  // persistent: one workgroup per CU
+  const int items = tiles_m * tiles_n * (e.splits > 1 ? e.splits : 1);
+  const int grid = items < n_cu ? items : n_cu;  // persistent: one workgroup per CU
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.M, g.N, g.K, (const bf16_t*)g.A, g.lda,
                      (const bf16_t*)g.B, g.ldb, e, tiles_m, tiles_n);
   FAX_LAUNCH_CHECK("gemm_mfma");
@@ -591,11 +621,21 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   return launch_mfma<BT, false, false, EK_STORE>(g, e, s);
 }
 
-int gemm_mfma(const GemmArgs& g, hipStream_t s) {
+int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
+  GemmArgs g = g0;
+  // Split the contraction?  Only the fp32-output form, with scratch from the caller and C stored
+  // densely; the partial products are then folded into C in a fixed order (and the column sums of
+  // B, if asked for, are left to the caller: gemm() takes them in a pass of their own).
+  const int splits = (g.c_f32 && g.split_ws && g.ldc == g.N && !g.colsum) ? gemm_split_count(g.M, g.N, g.K) : 1;
+  if (splits > 1) {
+    g.C = g.split_ws;
+    g.accumulate = false;
+  }
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
-            g.accumulate ? 1 : 0, g.colsum};
-  if (pick_tile(g) == 256) return dispatch<256>(g, e, s);
-  return dispatch<128>(g, e, s);
+            g.accumulate ? 1 : 0, g.colsum, splits, (size_t)g.M * g.N};
+  FAX_TRY(pick_tile(g) == 256 ? dispatch<256>(g, e, s) : dispatch<128>(g, e, s));
+  if (splits > 1) FAX_TRY(fold_partials(splits, (size_t)g.M * g.N, (const float*)g.split_ws, (float*)g0.C, g0.accumulate, s));
+  return FAX_OK;
 }
 
 }  // namespace fax

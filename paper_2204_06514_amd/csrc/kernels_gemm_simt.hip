@@ -110,7 +110,20 @@ static int gemm_dispatch(const GemmArgs& g, hipStream_t s) {
     set_error("fax_gemm: shape M=%d N=%d K=%d (dtype %d) does not tile for the MFMA kernel", g.M, g.N, g.K, g.dtype);
     return FAX_ERR_UNSUPPORTED;
   }
-  if (mfma) return gemm_mfma(g, s);
+  if (mfma) {
+    if (g.colsum && g.split_ws && g.c_f32 && g.ldc == g.N && gemm_split_count(g.M, g.N, g.K) > 1) {
+      // the split-K form does not carry the column sums of B: take them separately
+      if (!g.colsum_ws) {
+        set_error("gemm: column sums need scratch space");
+        return FAX_ERR_INVALID_ARG;
+      }
+      FAX_TRY(colsum(g.dtype, g.K, g.N, g.B, g.ldb, g.colsum, g.accumulate, g.colsum_ws, s));
+      GemmArgs h = g;
+      h.colsum = nullptr;
+      return gemm_mfma(h, s);
+    }
+    return gemm_mfma(g, s);
+  }
   if (g.colsum) {
     // no fused form here: take the column sums of B [K, N] in a pass of their own
     if (g.tb || !g.colsum_ws) {

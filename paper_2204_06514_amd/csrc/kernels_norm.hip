@@ -334,6 +334,18 @@ __global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, co
   }
 }
 
+int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s) {
+  if (n == 0) return FAX_OK;
+  if (n > (size_t)0x7fffffff) {
+    set_error("fold_partials: %zu elements", n);
+    return FAX_ERR_UNSUPPORTED;
+  }
+  hipLaunchKernelGGL(fold_partials_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, s, parts, (int)n, partial, out,
+                     (float*)nullptr, accumulate ? 1 : 0);
+  FAX_LAUNCH_CHECK("fold_partials");
+  return FAX_OK;
+}
+
 static int strips(int rows) { return max(1, min(CS_PARTS, (rows + 3) / 4)); }
 
 size_t ln_bwd_ws_bytes(int D) { return (size_t)2 * CS_PARTS * (size_t)D * sizeof(float); }

@@ -74,6 +74,8 @@ BF16_SMALL = [
     BlockShape(B=1, S=384, D=512, H=2, dh=128, F=256, dtype="bf16", sigma_w=0.02),
     # ragged everything: the scalar fallback kernels
     BlockShape(B=2, S=100, D=136, H=3, dh=24, F=200, dtype="bf16", sigma_w=0.05),
+    # many tokens, narrow layers: the weight-gradient products split their contraction (4 and 2 ways)
+    BlockShape(B=2, S=1024, D=256, H=4, dh=64, F=512, dtype="bf16", sigma_w=0.02),
 ]
 
 
@@ -83,3 +85,16 @@ def test_bf16_small_blocks(sh, generic):
     p, x, dy = make_block_inputs(sh, seed=2, generic=generic)
     out = run_block(sh, p, x, dy, partial=True)
     _check_block(sh, out, p, x, dy, "tanh", partial=True)
+
+
+def test_bf16_split_contraction_accumulates():
+    """Weight gradients whose contraction is split over workgroups, added onto existing values."""
+    sh = BF16_SMALL[3]
+    p, x, dy = make_block_inputs(sh, seed=5, generic=True)
+    rng = np.random.default_rng(1)
+    init = {k: rng.standard_normal(p[k].shape) * 0.5 for k in PARAM_NAMES}
+    out = run_block(sh, p, x, dy, accumulate=True, grads_init=init)
+    base = run_block(sh, p, x, dy)
+    for k in PARAM_NAMES:
+        ref = init[k].astype(np.float32).astype(np.float64) + base["grads"][k].astype(np.float64)
+        assert rel_max(out["grads"][k], ref) <= 1e-6, k
