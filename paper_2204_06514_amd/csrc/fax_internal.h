@@ -65,9 +65,14 @@ int gemm(const GemmArgs& g, hipStream_t s);
 int gemm_simt(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
 // A weight-gradient product of a narrow model has few output tiles and a very long contraction
-// (K = all tokens): it is then cut into `gemm_split_count` equal K ranges, each a full set of
-// tiles writing its own fp32 partial product, summed afterwards in a fixed order.  1 = no split.
-int gemm_split_count(int M, int N, int K);
+// (K = all tokens): it is then cut into K ranges, each a full set of tiles writing its own fp32
+// partial product (and partial column sums), summed afterwards in a fixed order.  The plan (tile
+// edge, number of ranges; 1 = no split) comes from a small cost model of the kernel.
+struct GemmSplitPlan {
+  int tile;    // 256 or 128; 0: shape not supported
+  int splits;
+};
+GemmSplitPlan gemm_split_plan(int M, int N, int K);
 size_t gemm_split_ws_bytes(int M, int N, int K);
 int gemm_mfma(const GemmArgs& g, hipStream_t s);
 
@@ -223,6 +228,7 @@ struct EpiArgs {
   float* colsum;
   int splits;           // K ranges (fp32-output form); range r writes to C + r * split_stride
   size_t split_stride;  // in elements
+  size_t colsum_stride; // likewise for the column sums: range r writes colsum + r * colsum_stride
 };
 
 template <typename T>

@@ -220,12 +220,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     lds_dma16(tile_base + k0 * b_kstride, b_lane_off[q], smem_addr + B_BASE + buf * LB::BYTES + (wave * NSB + q) * 1024);
   };
   // With the contraction split (fp32-output form) the work items are (K range, tile) pairs: item
-  // v is tile v % nt over slabs [r nk, (r + 1) nk), r = v / nt, and writes the partial product r.
+  // v is tile v % nt over slabs [r nkt / splits, (r + 1) nkt / splits), r = v / nt, nkt = K / GK,
+  // and writes the partial product r (and the partial column sums r).
   const int splits = e.splits > 1 ? e.splits : 1;
-  const int nk = K / GK / splits;
+  const int nk_total = K / GK;
+  auto k_range = [&](int item, int& first, int& count) {
+    const int r = item / nt;
+    first = (int)((unsigned)r * (unsigned)nk_total / (unsigned)splits);  // r < 32, nk_total < 2^25
+    count = (int)((unsigned)(r + 1) * (unsigned)nk_total / (unsigned)splits) - first;
+  };
   // A tile starts with slab 0 in A[0], B[0] and slab 1 in A[1], B[1].  Everything but B of slab 1
   // can be requested while the previous tile's epilogue still uses A[2] and B[1].
-  auto request_first_slabs = [&](const bf16_t* a_base, const bf16_t* b_base) {
+  auto request_first_slabs = [&](const bf16_t* a_base, const bf16_t* b_base, int nk) {
 #pragma unroll
     for (int q = 0; q < NSA; q++) dma_a_from(a_base, q, 0, 0);
 #pragma unroll
@@ -237,15 +243,21 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   };
 
   int tm_i, tn_i;
+  int k_first, nk_item;
   tile_of(blockIdx.x % nt, tm_i, tn_i);
-  size_t k_begin = (size_t)(blockIdx.x / nt) * nk * GK;
-  request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride);
+  k_range(blockIdx.x, k_first, nk_item);
+  size_t k_begin = (size_t)k_first * GK;
+  request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride, nk_item);
   for (int tile = blockIdx.x; tile < nt * splits; tile += gridDim.x) {
+  const int nk = nk_item;
   const int m0 = tm_i * BM, n0 = tn_i * BN;
   const bf16_t* const a_tile = a_tile_of(tm_i) + k_begin * a_kstride;
   const bf16_t* const b_tile = b_tile_of(tn_i) + k_begin * b_kstride;
   EpiArgs et = e;  // this item's view of the epilogue operands
-  if (em_kind(EM) == EK_F32) et.C = (float*)e.C + (size_t)(tile / nt) * e.split_stride;
+  if (em_kind(EM) == EK_F32) {
+    et.C = (float*)e.C + (size_t)(tile / nt) * e.split_stride;
+    if (EM & EM_COLSUM) et.colsum = e.colsum + (size_t)(tile / nt) * e.colsum_stride;
+  }
   auto dma_a = [&](int q, int k0, int buf) { dma_a_from(a_tile, q, k0, buf); };
   auto dma_b = [&](int q, int k0, int buf) { dma_b_from(b_tile, q, k0, buf); };
   lds_dma_wait();   // slab 0 and A of slab 1 (requested a whole epilogue ago, except for the first tile)
@@ -423,7 +435,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 #pragma unroll
         for (int j = 0; j < TN; j++) {
           const float v = cs[j] + xch[j * 32 + lane];
-          float* o = e.colsum + n0 + wn + j * 32 + lane;
+          float* o = et.colsum + n0 + wn + j * 32 + lane;
           *o = e.accumulate ? *o + v : v;
         }
       }
@@ -433,8 +445,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   if (tile + (int)gridDim.x < nt * splits) {
     const int next = tile + gridDim.x;
     tile_of(next % nt, tm_i, tn_i);
-    k_begin = (size_t)(next / nt) * nk * GK;
-    request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride);
+    k_range(next, k_first, nk_item);
+    k_begin = (size_t)k_first * GK;
+    request_first_slabs(a_tile_of(tm_i) + k_begin * a_kstride, b_tile_of(tn_i) + k_begin * b_kstride, nk_item);
   }
   // (lane index through an opaque copy: otherwise everything derived from it below is hoisted out of
   // the tile loop and kept in registers across the main loop, which has none to spare)
@@ -519,19 +532,37 @@ static int pick_tile_mn(int M, int N) {
   return 0;
 }
 
-int gemm_split_count(int M, int N, int K) {
-  const int bt = pick_tile_mn(M, N);
-  if (bt == 0 || K % GK) return 1;
-  const int tiles = (M / bt) * (N / bt), nk = K / GK;
-  if (2 * tiles > kCUs) return 1;  // at least half the CUs busy already
-  int s = 1;
-  while (2 * s * tiles <= kCUs && s < 16 && nk % (2 * s) == 0 && nk / (2 * s) >= 8) s *= 2;
-  return s;
+// Cost model behind the plan, in microseconds, from timings of this kernel on fp32-output
+// products: a K slab costs a workgroup 1.13 us at 256^2 and 0.66 us at 128^2 (a quarter of the
+// work at well under half the speed: four times the LDS traffic per flop), the fp32 epilogue 8 and
+// 3 us; workgroups run in rounds of one per CU; folding s partial products costs a launch plus
+// their bytes, written once and read once.
+GemmSplitPlan gemm_split_plan(int M, int N, int K) {
+  GemmSplitPlan best{pick_tile_mn(M, N), 1};
+  if (best.tile == 0 || K % GK) return best;
+  const int nkt = K / GK;
+  double best_t = 1e30;
+  for (int bt = 256; bt >= 128; bt /= 2) {
+    if (M % bt || N % bt) continue;
+    const double t_slab = bt == 256 ? 1.13 : 0.66, t_epi = bt == 256 ? 8.0 : 3.0;
+    const long long tiles = (long long)(M / bt) * (N / bt);
+    for (int s = 1; s <= 32 && nkt / s >= 8; s++) {
+      const long long rounds = (tiles * s + kCUs - 1) / kCUs;
+      double t = rounds * ((nkt + s - 1) / s * t_slab + t_epi);
+      if (s > 1) t += 10.0 + (2.0 * s + 1.0) * M * N * 4.0 / 3.0e6;
+      if (t < best_t * 0.97) {  // a split has to pay for itself
+        best_t = t;
+        best = GemmSplitPlan{bt, s};
+      }
+    }
+  }
+  return best;
 }
 
+// partial products, then partial column sums
 size_t gemm_split_ws_bytes(int M, int N, int K) {
-  const int s = gemm_split_count(M, N, K);
-  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+  const int s = gemm_split_plan(M, N, K).splits;
+  return s > 1 ? (size_t)s * ((size_t)M * N + N) * sizeof(float) : 0;
 }
 
 static int pick_tile(const GemmArgs& g) { return pick_tile_mn(g.M, g.N); }
@@ -624,17 +655,25 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
 int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   // Split the contraction?  Only the fp32-output form, with scratch from the caller and C stored
-  // densely; the partial products are then folded into C in a fixed order (and the column sums of
-  // B, if asked for, are left to the caller: gemm() takes them in a pass of their own).
-  const int splits = (g.c_f32 && g.split_ws && g.ldc == g.N && !g.colsum) ? gemm_split_count(g.M, g.N, g.K) : 1;
+  // densely; the partial products (and partial column sums) are then folded in a fixed order.
+  GemmSplitPlan plan{pick_tile(g), 1};
+  if (g.c_f32 && g.split_ws && g.ldc == g.N) plan = gemm_split_plan(g.M, g.N, g.K);
+  const int splits = plan.splits;
+  const size_t mn = (size_t)g.M * g.N;
+  float* const part_c = (float*)g.split_ws;
+  float* const part_cs = part_c + (size_t)splits * mn;
   if (splits > 1) {
-    g.C = g.split_ws;
+    g.C = part_c;
+    if (g.colsum) g.colsum = part_cs;
     g.accumulate = false;
   }
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
-            g.accumulate ? 1 : 0, g.colsum, splits, (size_t)g.M * g.N};
-  FAX_TRY(pick_tile(g) == 256 ? dispatch<256>(g, e, s) : dispatch<128>(g, e, s));
-  if (splits > 1) FAX_TRY(fold_partials(splits, (size_t)g.M * g.N, (const float*)g.split_ws, (float*)g0.C, g0.accumulate, s));
+            g.accumulate ? 1 : 0, g.colsum, splits, mn, (size_t)g.N};
+  FAX_TRY(plan.tile == 256 ? dispatch<256>(g, e, s) : dispatch<128>(g, e, s));
+  if (splits > 1) {
+    FAX_TRY(fold_partials(splits, mn, part_c, (float*)g0.C, g0.accumulate, s));
+    if (g0.colsum) FAX_TRY(fold_partials(splits, (size_t)g.N, part_cs, g0.colsum, g0.accumulate, s));
+  }
   return FAX_OK;
 }
 

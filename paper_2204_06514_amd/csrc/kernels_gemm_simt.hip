@@ -111,17 +111,6 @@ static int gemm_dispatch(const GemmArgs& g, hipStream_t s) {
     return FAX_ERR_UNSUPPORTED;
   }
   if (mfma) {
-    if (g.colsum && g.split_ws && g.c_f32 && g.ldc == g.N && gemm_split_count(g.M, g.N, g.K) > 1) {
-      // the split-K form does not carry the column sums of B: take them separately
-      if (!g.colsum_ws) {
-        set_error("gemm: column sums need scratch space");
-        return FAX_ERR_INVALID_ARG;
-      }
-      FAX_TRY(colsum(g.dtype, g.K, g.N, g.B, g.ldb, g.colsum, g.accumulate, g.colsum_ws, s));
-      GemmArgs h = g;
-      h.colsum = nullptr;
-      return gemm_mfma(h, s);
-    }
     return gemm_mfma(g, s);
   }
   if (g.colsum) {

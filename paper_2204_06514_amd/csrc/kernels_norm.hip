@@ -334,8 +334,39 @@ __global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, co
   }
 }
 
+// The same for long vectors, four elements per thread: out[i] (+)= (partial[0][i] + partial[1][i] + ...).
+__global__ __launch_bounds__(256) void fold_partials_vec_kernel(int parts, size_t n4, const float4* __restrict__ partial,
+                                                                float4* __restrict__ out, int accumulate) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  float4 s = partial[i];
+#pragma unroll 4
+  for (int p = 1; p < parts; p++) {
+    const float4 v = partial[(size_t)p * n4 + i];
+    s.x += v.x;
+    s.y += v.y;
+    s.z += v.z;
+    s.w += v.w;
+  }
+  if (accumulate) {
+    const float4 o = out[i];
+    s.x += o.x;
+    s.y += o.y;
+    s.z += o.z;
+    s.w += o.w;
+  }
+  out[i] = s;
+}
+
 int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s) {
   if (n == 0) return FAX_OK;
+  if (n % 4 == 0 && n >= 4096 && ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0 &&
+      n / 4 / 256 < 0x7fffffff) {
+    hipLaunchKernelGGL(fold_partials_vec_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s, parts, n / 4,
+                       (const float4*)partial, (float4*)out, accumulate ? 1 : 0);
+    FAX_LAUNCH_CHECK("fold_partials");
+    return FAX_OK;
+  }
   if (n > (size_t)0x7fffffff) {
     set_error("fold_partials: %zu elements", n);
     return FAX_ERR_UNSUPPORTED;

@@ -74,7 +74,7 @@ BF16_SMALL = [
     BlockShape(B=1, S=384, D=512, H=2, dh=128, F=256, dtype="bf16", sigma_w=0.02),
     # ragged everything: the scalar fallback kernels
     BlockShape(B=2, S=100, D=136, H=3, dh=24, F=200, dtype="bf16", sigma_w=0.05),
-    # many tokens, narrow layers: the weight-gradient products split their contraction (4 and 2 ways)
+    # many tokens, narrow layers: the weight-gradient products split their contraction over several workgroups per tile
     BlockShape(B=2, S=1024, D=256, H=4, dh=64, F=512, dtype="bf16", sigma_w=0.02),
 ]
 
