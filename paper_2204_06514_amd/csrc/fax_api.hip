@@ -334,7 +334,7 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
 
 // ---- model ----------------------------------------------------------------------------------
 struct TrainWs {
-  size_t xs, saved, hf, muf, rstdf, logits, row_loss, dcur, dhf, blk, total;
+  size_t xs, saved, hf, muf, rstdf, logits, row_loss, dcur, dhf, blk, headsplit, total;
   size_t x_stride, saved_stride;
 };
 
@@ -359,6 +359,7 @@ static void train_layout(const FaxModelDims& m, TrainWs* W) {
   W->dcur = take(z.T * z.D * z.es);
   W->dhf = take(z.T * z.D * z.es);
   W->blk = take(B.total);
+  W->headsplit = take(gemm_split_ws_bytes(m.V, (int)z.D, (int)z.T));  // the embedding gradient's product may split K
   W->total = o;
 }
 
@@ -635,6 +636,7 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   g.M = V; g.N = D; g.K = T;
   g.A = w + W.logits; g.lda = V; g.B = w + W.hf; g.ldb = D; g.C = grads->tok_emb; g.ldc = D; g.c_f32 = true;
   g.accumulate = acc;
+  g.split_ws = W.headsplit < W.total ? w + W.headsplit : nullptr;
   FAX_TRY(gemm(g, s));
   g = GemmArgs(); g.dtype = d.dtype;
   g.M = T; g.N = D; g.K = V;

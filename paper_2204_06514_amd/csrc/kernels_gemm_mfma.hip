@@ -25,6 +25,8 @@
 // consecutive columns n = 8 g + 4 (l >> 5) + 0..3 -- a 16-byte unit for the epilogue.
 #include <type_traits>
 
+#include <algorithm>
+
 #include "fax_internal.h"
 
 namespace fax {
@@ -559,10 +561,23 @@ GemmSplitPlan gemm_split_plan(int M, int N, int K) {
   return best;
 }
 
+// One dimension an odd multiple of 128 and the rest big enough for 256^2 tiles: the product is
+// computed as two, the bulk on 256^2 tiles and the last 128 rows (1) or columns (2) on 128^2 tiles.
+static int tail_dim(int M, int N) {
+  if (M % 256 == 128 && N % 256 == 0 && pick_tile_mn(M - 128, N) == 256) return 1;
+  if (N % 256 == 128 && M % 256 == 0 && pick_tile_mn(M, N - 128) == 256) return 2;
+  return 0;
+}
+
 // partial products, then partial column sums
-size_t gemm_split_ws_bytes(int M, int N, int K) {
+static size_t split_ws_bytes_1(int M, int N, int K) {
   const int s = gemm_split_plan(M, N, K).splits;
   return s > 1 ? (size_t)s * ((size_t)M * N + N) * sizeof(float) : 0;
+}
+
+size_t gemm_split_ws_bytes(int M, int N, int K) {
+  if (tail_dim(M, N) == 1) return std::max(split_ws_bytes_1(M - 128, N, K), split_ws_bytes_1(128, N, K));
+  return split_ws_bytes_1(M, N, K);  // a column strip keeps the leading dimension of C: no split there
 }
 
 static int pick_tile(const GemmArgs& g) { return pick_tile_mn(g.M, g.N); }
@@ -652,7 +667,40 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   return launch_mfma<BT, false, false, EK_STORE>(g, e, s);
 }
 
+static const void* offset(const void* p, size_t elements, size_t elem_bytes) {
+  return p ? (const char*)p + elements * elem_bytes : nullptr;
+}
+static void* offset(void* p, size_t elements, size_t elem_bytes) { return p ? (char*)p + elements * elem_bytes : nullptr; }
+
 int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
+  if (const int td = tail_dim(g0.M, g0.N)) {
+    const size_t cb = g0.c_f32 ? 4 : 2;
+    for (int part = 0; part < 2; part++) {
+      GemmArgs h = g0;
+      if (td == 1) {  // rows [m0, m0 + M')
+        const size_t m0 = part ? g0.M - 128 : 0;
+        h.M = part ? 128 : g0.M - 128;
+        h.A = offset(g0.A, g0.ta ? m0 : m0 * g0.lda, 2);
+        h.C = offset(g0.C, m0 * g0.ldc, cb);
+        h.R = offset(g0.R, m0 * g0.ldr, 2);
+        h.C2 = offset(g0.C2, m0 * g0.ldc2, 2);
+        h.U = offset(g0.U, m0 * g0.ldu, 2);
+        if (part) h.colsum = nullptr;  // the column sums of B are complete after the first product
+      } else {        // columns [n0, n0 + N')
+        const size_t n0 = part ? g0.N - 128 : 0;
+        h.N = part ? 128 : g0.N - 128;
+        h.B = offset(g0.B, g0.tb ? n0 * g0.ldb : n0, 2);
+        h.C = offset(g0.C, n0, cb);
+        h.bias = offset(g0.bias, n0, 2);
+        h.R = offset(g0.R, n0, 2);
+        h.C2 = offset(g0.C2, n0, 2);
+        h.U = offset(g0.U, n0, 2);
+        if (g0.colsum) h.colsum = g0.colsum + n0;
+      }
+      FAX_TRY(gemm_mfma(h, s));  // (neither part has a tail of its own)
+    }
+    return FAX_OK;
+  }
   GemmArgs g = g0;
   // Split the contraction?  Only the fp32-output form, with scratch from the caller and C stored
   // densely; the partial products (and partial column sums) are then folded in a fixed order.

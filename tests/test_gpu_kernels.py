@@ -40,6 +40,11 @@ GEMM_CASES = [
     ("bf16", fax.PATH_MFMA, 0, 0, 4352, 4352, 64),
     ("bf16", fax.PATH_MFMA, 0, 1, 4352, 4352, 128),
     ("bf16", fax.PATH_MFMA, 1, 0, 4352, 4352, 192),
+    # one dimension an odd multiple of 128: 256-tiles for the bulk, 128-tiles for the last strip
+    ("bf16", fax.PATH_MFMA, 0, 0, 4224, 2048, 128),
+    ("bf16", fax.PATH_MFMA, 0, 1, 2048, 4224, 64),
+    ("bf16", fax.PATH_MFMA, 1, 0, 4224, 2048, 192),
+    ("bf16", fax.PATH_MFMA, 1, 1, 2048, 4224, 128),
 ]
 
 
