@@ -86,7 +86,7 @@ typedef struct FaxSavedLayout {
   size_t lse;   /* [B, H, S]   fp32 log-sum-exp of the scaled masked scores */
   size_t x1;    /* [T, D]      x + ctx Wo + bo */
   size_t h2;    /* [T, D]      LN2(x1) */
-  size_t u;     /* [T, F]      h2 W1 + b1 */
+  size_t dgelu; /* [T, F]      gelu'(u), u = h2 W1 + b1: all the backward pass needs of u */
   size_t a;     /* [T, F]      gelu(u) */
   size_t mu1, rstd1, mu2, rstd2; /* [T] fp32 each */
   size_t total; /* bytes to allocate */

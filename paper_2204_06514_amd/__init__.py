@@ -43,7 +43,7 @@ class FaxBlockTensors(C.Structure):
 
 
 class FaxSavedLayout(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("h1", "qkv", "ctx", "lse", "x1", "h2", "u", "a",
+    _fields_ = [(n, C.c_size_t) for n in ("h1", "qkv", "ctx", "lse", "x1", "h2", "dgelu", "a",
                                           "mu1", "rstd1", "mu2", "rstd2", "total")]
 
 

@@ -121,7 +121,7 @@ static void saved_layout(const FaxBlockDims& d, FaxSavedLayout* L) {
   L->lse = take((size_t)d.B * d.H * d.S * 4);
   L->x1 = take(z.T * z.D * z.es);
   L->h2 = take(z.T * z.D * z.es);
-  L->u = take(z.T * z.F * z.es);
+  L->dgelu = take(z.T * z.F * z.es);
   L->a = take(z.T * z.F * z.es);
   L->mu1 = take(z.T * 4);
   L->rstd1 = take(z.T * 4);
@@ -257,10 +257,10 @@ static int block_fwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   FAX_TRY(gemm(g, s));
   FAX_TRY(ln_fwd(d.dtype, T, D, saved + L.x1, p.ln2_g, p.ln2_b, d.ln_eps, saved + L.h2, (float*)(saved + L.mu2),
                  (float*)(saved + L.rstd2), s));
-  // u = h2 W1 + b1 ; a = gelu(u)
+  // u = h2 W1 + b1 ; a = gelu(u), kept together with gelu'(u)
   g = GemmArgs(); g.dtype = d.dtype; g.gelu_form = d.gelu;
   g.M = T; g.N = F; g.K = D;
-  g.A = saved + L.h2; g.lda = D; g.B = p.w1; g.ldb = F; g.C = saved + L.u; g.ldc = F; g.bias = p.b1;
+  g.A = saved + L.h2; g.lda = D; g.B = p.w1; g.ldb = F; g.C = saved + L.dgelu; g.ldc = F; g.bias = p.b1;
   g.epi = EPI_GELU; g.C2 = saved + L.a; g.ldc2 = F;
   FAX_TRY(gemm(g, s));
   // y = x1 + a W2 + b2
@@ -308,7 +308,7 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   FAX_TRY(wgrad(saved + L.a, F, F, dy, D, D, gr.w2, gr.b2));
   {
     GemmArgs g = dgrad(dy, D, D, p.w2, D, F, du);  // du = (dy W2^T) * gelu'(u)
-    g.epi = EPI_DGELU; g.U = saved + L.u; g.ldu = F; g.gelu_form = d.gelu;
+    g.epi = EPI_DGELU; g.U = saved + L.dgelu; g.ldu = F;
     FAX_TRY(gemm(g, s));
   }
   // feed-forward input projection

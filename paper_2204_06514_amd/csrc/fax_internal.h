@@ -34,8 +34,8 @@ enum { PATH_AUTO = 0, PATH_SIMT = 1, PATH_MFMA = 2 };
 // C[M,N] = op(A) op(B) in fp32, then (in this order):
 //   C2 = acc                       (EPI_NONE with C2: the pre-bias partial product)
 //   acc += bias[n]; acc += R[m,n]
-//   EPI_GELU : C = acc, C2 = gelu(acc)
-//   EPI_DGELU: C = acc * gelu'(U[m,n])
+//   EPI_GELU : C = gelu'(acc), C2 = gelu(acc)   (the backward pass needs the derivative, never acc itself)
+//   EPI_DGELU: C = acc * U[m,n]                 (U: the derivative stored by EPI_GELU)
 //   otherwise: C = acc (fp32 C may accumulate)
 struct GemmArgs {
   int dtype = FAX_BF16;
@@ -237,10 +237,10 @@ __device__ __forceinline__ void epilogue_store(const EpiArgs& e, int m, int n, f
   if (e.bias) acc += to_f(((const T*)e.bias)[n]);
   if (e.R) acc += to_f(((const T*)e.R)[(size_t)m * e.ldr + n]);
   if (e.epi == EPI_GELU) {
-    ((T*)e.C)[(size_t)m * e.ldc + n] = from_f<T>(acc);
+    ((T*)e.C)[(size_t)m * e.ldc + n] = from_f<T>(gelu_grad_f(acc, e.gelu_form));
     ((T*)e.C2)[(size_t)m * e.ldc2 + n] = from_f<T>(gelu_f(acc, e.gelu_form));
   } else {
-    if (e.epi == EPI_DGELU) acc *= gelu_grad_f(to_f(((const T*)e.U)[(size_t)m * e.ldu + n]), e.gelu_form);
+    if (e.epi == EPI_DGELU) acc *= to_f(((const T*)e.U)[(size_t)m * e.ldu + n]);
     if (e.c_f32) {
       float* c = (float*)e.C + (size_t)m * e.ldc + n;
       *c = e.accumulate ? *c + acc : acc;

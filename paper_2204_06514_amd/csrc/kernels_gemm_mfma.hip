@@ -88,14 +88,14 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
 // in the store loop may hang on a run-time condition: stores count towards the same counter as
 // loads on this target, so the conservative wait the compiler places where branches that contain
 // loads rejoin would also wait for every earlier store to be acknowledged, once per row.
-enum { EK_STORE = 0, EK_GELU_TANH = 1, EK_GELU_ERF = 2, EK_DGELU_TANH = 3, EK_DGELU_ERF = 4, EK_F32 = 5 };
+enum { EK_STORE = 0, EK_GELU_TANH = 1, EK_GELU_ERF = 2, EK_DGELU = 3, EK_F32 = 5 };
 enum {
   EM_RES = 8,  // bf16 kinds: add the residual R;  EK_F32: add to what C already holds
   EM_C2 = 16,  // EK_STORE: also write the plain product (before bias and residual) to C2
   EM_COLSUM = 32  // EK_F32, B stored [K, N]: also colsum[n] (+)= sum_k B[k, n]
 };
 constexpr int em_kind(int em) { return em & 7; }
-constexpr bool em_dgelu(int em) { return em_kind(em) == EK_DGELU_TANH || em_kind(em) == EK_DGELU_ERF; }
+constexpr bool em_dgelu(int em) { return em_kind(em) == EK_DGELU; }
 constexpr bool em_gelu(int em) { return em_kind(em) == EK_GELU_TANH || em_kind(em) == EK_GELU_ERF; }
 
 // tanh-form GELU through the logistic function: (1 + tanh z) / 2 = 1 / (1 + exp(-2 z)), one
@@ -104,10 +104,11 @@ __device__ __forceinline__ float sigmoid2z(float u) {
   const float z2 = 1.5957691216057308f * (u + 0.044715f * u * u * u);  // 2 sqrt(2/pi) (u + k u^3)
   return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z2));
 }
-__device__ __forceinline__ float gelu_tanh_fast(float u) { return u * sigmoid2z(u); }
-__device__ __forceinline__ float gelu_tanh_grad_fast(float u) {
+// gelu(u) and gelu'(u) from the one logistic value
+__device__ __forceinline__ void gelu_tanh_both(float u, float& g, float& dg) {
   const float sg = sigmoid2z(u);
-  return sg + u * sg * (1.f - sg) * 1.5957691216057308f * (1.f + 0.134145f * u * u);
+  g = u * sg;
+  dg = sg + (g - g * sg) * (1.5957691216057308f + 0.21406149f * u * u);  // 2 sqrt(2/pi) (1 + 3 k u^2)
 }
 
 // Four consecutive columns n..n+3 of row m at once: 8-byte bf16 loads and stores.
@@ -121,7 +122,7 @@ __device__ __forceinline__ void st_bf16x4(void* base, size_t idx, float4 a) {
   v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
   *reinterpret_cast<bf16x4*>((bf16_t*)base + idx) = v;
 }
-// `side` is the row's residual (R) or, for the GELU' flavours, its pre-activation (U), fetched by
+// `side` is the row's residual (R) or, for the GELU' flavour, the stored derivative (U), fetched by
 // the caller ahead of time so that its latency overlaps the LDS turn-around.
 // For the fp32 flavour (plain product, optionally added to what C holds) `side` is the old C.
 template <int EM>
@@ -137,28 +138,22 @@ __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, f
   if (!em_dgelu(EM) && (EM & EM_RES)) {
     a.x += side.x; a.y += side.y; a.z += side.z; a.w += side.w;
   }
-  if (em_gelu(EM)) {
-    st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
-    float4 g;
+  if (em_gelu(EM)) {  // C = gelu'(acc), C2 = gelu(acc)
+    float4 g, dg;
     if (KIND == EK_GELU_TANH) {
-      g = make_float4(gelu_tanh_fast(a.x), gelu_tanh_fast(a.y), gelu_tanh_fast(a.z), gelu_tanh_fast(a.w));
+      gelu_tanh_both(a.x, g.x, dg.x); gelu_tanh_both(a.y, g.y, dg.y);
+      gelu_tanh_both(a.z, g.z, dg.z); gelu_tanh_both(a.w, g.w, dg.w);
     } else {
       g = make_float4(gelu_f(a.x, FAX_GELU_ERF), gelu_f(a.y, FAX_GELU_ERF), gelu_f(a.z, FAX_GELU_ERF),
                       gelu_f(a.w, FAX_GELU_ERF));
+      dg = make_float4(gelu_grad_f(a.x, FAX_GELU_ERF), gelu_grad_f(a.y, FAX_GELU_ERF), gelu_grad_f(a.z, FAX_GELU_ERF),
+                       gelu_grad_f(a.w, FAX_GELU_ERF));
     }
+    st_bf16x4(e.C, (size_t)m * e.ldc + n, dg);
     st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, g);
     return;
   }
-  if (em_dgelu(EM)) {
-    const float4 u = side;
-    if (KIND == EK_DGELU_TANH) {
-      a.x *= gelu_tanh_grad_fast(u.x); a.y *= gelu_tanh_grad_fast(u.y);
-      a.z *= gelu_tanh_grad_fast(u.z); a.w *= gelu_tanh_grad_fast(u.w);
-    } else {
-      a.x *= gelu_grad_f(u.x, FAX_GELU_ERF); a.y *= gelu_grad_f(u.y, FAX_GELU_ERF);
-      a.z *= gelu_grad_f(u.z, FAX_GELU_ERF); a.w *= gelu_grad_f(u.w, FAX_GELU_ERF);
-    }
-  }
+  if (em_dgelu(EM)) { a.x *= side.x; a.y *= side.y; a.z *= side.z; a.w *= side.w; }
   st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
 }
 
@@ -535,8 +530,8 @@ static int pick_tile_mn(int M, int N) {
 }
 
 // Cost model behind the plan, in microseconds, from timings of this kernel on fp32-output
-// products: a K slab costs a workgroup 1.13 us at 256^2 and 0.66 us at 128^2 (a quarter of the
-// work at well under half the speed: four times the LDS traffic per flop), the fp32 epilogue 8 and
+// products: a K slab costs a workgroup 1.55 us at 256^2 and 0.66 us at 128^2 (a quarter of the
+// work at not even half the time: twice the LDS traffic per flop), the fp32 epilogue 8 and
 // 3 us; workgroups run in rounds of one per CU; folding s partial products costs a launch plus
 // their bytes, written once and read once.
 GemmSplitPlan gemm_split_plan(int M, int N, int K) {
@@ -546,7 +541,7 @@ GemmSplitPlan gemm_split_plan(int M, int N, int K) {
   double best_t = 1e30;
   for (int bt = 256; bt >= 128; bt /= 2) {
     if (M % bt || N % bt) continue;
-    const double t_slab = bt == 256 ? 1.13 : 0.66, t_epi = bt == 256 ? 8.0 : 3.0;
+    const double t_slab = bt == 256 ? 1.55 : 0.66, t_epi = bt == 256 ? 8.0 : 3.0;
     const long long tiles = (long long)(M / bt) * (N / bt);
     for (int s = 1; s <= 32 && nkt / s >= 8; s++) {
       const long long rounds = (tiles * s + kCUs - 1) / kCUs;
@@ -636,7 +631,7 @@ static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   if (g.epi == EPI_GELU)
     return erf ? launch_mfma<BT, true, false, EK_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EK_GELU_TANH>(g, e, s);
   if (g.epi == EPI_DGELU)
-    return erf ? launch_mfma<BT, true, true, EK_DGELU_ERF>(g, e, s) : launch_mfma<BT, true, true, EK_DGELU_TANH>(g, e, s);
+    return launch_mfma<BT, true, true, EK_DGELU>(g, e, s);
   if (g.c_f32 && g.colsum)
     return g.accumulate ? launch_mfma<BT, false, false, EK_F32 | EM_RES | EM_COLSUM>(g, e, s)
                         : launch_mfma<BT, false, false, EK_F32 | EM_COLSUM>(g, e, s);

@@ -84,7 +84,7 @@ def run_block(sh, p, x, dy, gelu=None, partial=False, accumulate=False, grads_in
            "grads": {k: to_np(v) for k, v in gd.items()}}
     sv = {"h1": (lay.h1, (T, sh.D), td), "qkv": (lay.qkv, (T, 3 * Hd), td), "ctx": (lay.ctx, (T, Hd), td),
           "lse": (lay.lse, (sh.B, sh.H, sh.S), torch.float32), "x1": (lay.x1, (T, sh.D), td),
-          "h2": (lay.h2, (T, sh.D), td), "u": (lay.u, (T, sh.F), td), "a": (lay.a, (T, sh.F), td)}
+          "h2": (lay.h2, (T, sh.D), td), "dgelu": (lay.dgelu, (T, sh.F), td), "a": (lay.a, (T, sh.F), td)}
     out["saved"] = {k: to_np(view_bytes(saved, o, s, t)) for k, (o, s, t) in sv.items()}
     bl = fax.fax_block_bwd_layout(dims)
     bw = {"du": (bl.du, (T, sh.F)), "dh2": (bl.dh2, (T, sh.D)), "dx1": (bl.dx1, (T, sh.D)),

@@ -22,8 +22,9 @@ def _check_block(sh, out, p, x, dy, gelu, partial=False):
     for k in PARAM_NAMES:
         report["d" + k] = err(out["grads"][k], g[k], sh.dtype)
     flat = lambda a: a.reshape(-1, a.shape[-1])
-    for k in ("h1", "qkv", "ctx", "x1", "h2", "u", "a"):
+    for k in ("h1", "qkv", "ctx", "x1", "h2", "a"):
         report["saved." + k] = err(out["saved"][k], flat(c[k]), sh.dtype)
+    report["saved.dgelu"] = err(out["saved"]["dgelu"], flat(orc.gelu_grad(c["u"], gelu)), sh.dtype)
     for k in ("du", "dh2", "dx1", "dctx", "dqkv", "dh1"):
         report["bwd." + k] = err(out["bwd"][k], flat(it[k]), sh.dtype)
     if partial:

@@ -77,8 +77,9 @@ def test_cfg3_large_block_full_size():
     rep = {"y": rel_fro(out["y"], y), "dx": rel_fro(out["dx"], dx)}
     for k in PARAM_NAMES:
         rep["d" + k] = rel_fro(out["grads"][k], g[k])
-    for k in ("qkv", "ctx", "x1", "u", "a"):
+    for k in ("qkv", "ctx", "x1", "a"):
         rep["saved." + k] = rel_fro(out["saved"][k], flat(c[k]))
+    rep["saved.dgelu"] = rel_fro(out["saved"]["dgelu"], flat(orc.gelu_grad(c["u"])))
     for k in ("du", "dh2", "dx1", "dctx", "dqkv", "dh1"):
         rep["bwd." + k] = rel_fro(out["bwd"][k], flat(it[k]))
     _assert_all(rep)

@@ -51,7 +51,7 @@ def test_saved_layout_is_disjoint_and_sized():
     lay = fax.fax_block_saved_layout(d)
     T, D, Hd, F = 128, 128, 128, 512
     sizes = {"h1": T * D * 2, "qkv": T * 3 * Hd * 2, "ctx": T * Hd * 2, "lse": 2 * 4 * 64 * 4, "x1": T * D * 2,
-             "h2": T * D * 2, "u": T * F * 2, "a": T * F * 2, "mu1": T * 4, "rstd1": T * 4, "mu2": T * 4, "rstd2": T * 4}
+             "h2": T * D * 2, "dgelu": T * F * 2, "a": T * F * 2, "mu1": T * 4, "rstd1": T * 4, "mu2": T * 4, "rstd2": T * 4}
     spans = sorted((getattr(lay, k), getattr(lay, k) + n) for k, n in sizes.items())
     for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
         assert a1 <= b0
