@@ -153,59 +153,113 @@ int ln_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const v
 // ---------------------------------------------------------------------------------------------
 // Backward, row part: dx = rstd (g - mean(g) - xhat mean(g xhat)) [+ dres], g = dh * gamma.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int TPR>
-__global__ __launch_bounds__(LN_THREADS) void ln_bwd_dx_kernel(int rows, int D, const T* __restrict__ dh,
-                                                               const T* __restrict__ x, const float* __restrict__ mu,
-                                                               const float* __restrict__ rstd,
-                                                               const T* __restrict__ gamma, const T* __restrict__ dres,
-                                                               T* __restrict__ dx) {
+// With the parameter gradients folded in: a workgroup walks over row blocks b,
+// b + gridDim.x, ... and every thread keeps the running sums of dh * xhat (-> dgamma) and dh
+// (-> dbeta) for the columns it owns; dh and x are read once for all three results.  At the end
+// the row groups of the workgroup are combined through LDS and one partial row per workgroup is
+// written: partial[0][blockIdx.x][D] (dgamma), partial[1][blockIdx.x][D] (dbeta).
+// NV: 16-byte vectors per thread and row (D <= TPR * NV * V::N).
+template <typename T, int TPR, int NV>
+__global__ __launch_bounds__(LN_THREADS) void ln_bwd_fused_kernel(int rows, int D, const T* __restrict__ dh,
+                                                                  const T* __restrict__ x, const float* __restrict__ mu,
+                                                                  const float* __restrict__ rstd,
+                                                                  const T* __restrict__ gamma, const T* __restrict__ dres,
+                                                                  T* __restrict__ dx, float* __restrict__ partial) {
   using V = Vec16<T>;
-  __shared__ float red[LN_THREADS / 64];
   constexpr int RPB = LN_THREADS / TPR;
-  const int tr = threadIdx.x % TPR;
-  const int row = blockIdx.x * RPB + threadIdx.x / TPR;
-  const bool live = row < rows;
+  constexpr int NACC = NV * V::N * 2;  // running sums per thread
+  __shared__ float red[LN_THREADS / 64];
+  __shared__ float comb[RPB > 1 ? (RPB - 1) * NACC * TPR : 1];
+  const int tr = threadIdx.x % TPR, rg = threadIdx.x / TPR;
   const int nvec = D / V::N;
-  const size_t off = (size_t)(live ? row : 0) * D;
-  const float m = live ? mu[row] : 0.f, r = live ? rstd[row] : 0.f;
-  V dv[LN_MAXV], xv[LN_MAXV];
-  float s1 = 0.f, s2 = 0.f;
+  float ag[NV][V::N], ab[NV][V::N];
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; i++) {
-    const int c = tr + i * TPR;
-    if (c < nvec) {
-      V gv;
-      gv.load(gamma + c * V::N);
-      dv[i].load(dh + off + c * V::N);
-      xv[i].load(x + off + c * V::N);
+  for (int i = 0; i < NV; i++)
 #pragma unroll
-      for (int e = 0; e < V::N; e++) {
-        const float xh = (xv[i].get(e) - m) * r;
-        const float g = dv[i].get(e) * gv.get(e);
-        s1 += g;
-        s2 += g * xh;
+    for (int e = 0; e < V::N; e++) ag[i][e] = ab[i][e] = 0.f;
+  for (int rb = blockIdx.x; rb * RPB < rows; rb += gridDim.x) {  // trip count uniform over the workgroup
+    const int row = rb * RPB + rg;
+    const bool live = row < rows;
+    const size_t off = (size_t)(live ? row : 0) * D;
+    const float m = live ? mu[row] : 0.f, r = live ? rstd[row] : 0.f;
+    V dv[NV], xv[NV];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      const int c = tr + i * TPR;
+      if (c < nvec) {
+        V gv;
+        gv.load(gamma + c * V::N);
+        dv[i].load(dh + off + c * V::N);
+        xv[i].load(x + off + c * V::N);
+#pragma unroll
+        for (int e = 0; e < V::N; e++) {
+          const float xh = (xv[i].get(e) - m) * r;
+          const float g = dv[i].get(e) * gv.get(e);
+          s1 += g;
+          s2 += g * xh;
+        }
+      }
+    }
+    const float m1 = row_sum<TPR>(s1, red) / D;
+    const float m2 = row_sum<TPR>(s2, red) / D;
+    if (live) {
+#pragma unroll
+      for (int i = 0; i < NV; i++) {
+        const int c = tr + i * TPR;
+        if (c < nvec) {
+          V gv, o, rv;
+          gv.load(gamma + c * V::N);
+          if (dres) rv.load(dres + off + c * V::N);
+#pragma unroll
+          for (int e = 0; e < V::N; e++) {
+            const float xh = (xv[i].get(e) - m) * r;
+            const float dhe = dv[i].get(e);
+            float d = r * (dhe * gv.get(e) - m1 - xh * m2);
+            if (dres) d += rv.get(e);
+            o.set(e, d);
+            ag[i][e] += dhe * xh;
+            ab[i][e] += dhe;
+          }
+          o.store(dx + off + c * V::N);
+        }
       }
     }
   }
-  const float m1 = row_sum<TPR>(s1, red) / D;
-  const float m2 = row_sum<TPR>(s2, red) / D;
-  if (!live) return;
+  if (RPB > 1) {
+    __syncthreads();
+    if (rg > 0) {
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; i++) {
+      for (int i = 0; i < NV; i++)
+#pragma unroll
+        for (int e = 0; e < V::N; e++) {
+          comb[(((rg - 1) * NV + i) * V::N * 2 + e) * TPR + tr] = ag[i][e];
+          comb[(((rg - 1) * NV + i) * V::N * 2 + V::N + e) * TPR + tr] = ab[i][e];
+        }
+    }
+    __syncthreads();
+    if (rg > 0) return;
+#pragma unroll
+    for (int g = 0; g < RPB - 1; g++)
+#pragma unroll
+      for (int i = 0; i < NV; i++)
+#pragma unroll
+        for (int e = 0; e < V::N; e++) {
+          ag[i][e] += comb[((g * NV + i) * V::N * 2 + e) * TPR + tr];
+          ab[i][e] += comb[((g * NV + i) * V::N * 2 + V::N + e) * TPR + tr];
+        }
+  }
+  float* pg = partial + (size_t)blockIdx.x * D;
+  float* pb = partial + ((size_t)gridDim.x + blockIdx.x) * D;
+#pragma unroll
+  for (int i = 0; i < NV; i++) {
     const int c = tr + i * TPR;
     if (c < nvec) {
-      V gv, o, rv;
-      gv.load(gamma + c * V::N);
-      if (dres) rv.load(dres + off + c * V::N);
 #pragma unroll
-      for (int e = 0; e < V::N; e++) {
-        const float xh = (xv[i].get(e) - m) * r;
-        const float g = dv[i].get(e) * gv.get(e);
-        float d = r * (g - m1 - xh * m2);
-        if (dres) d += rv.get(e);
-        o.set(e, d);
+      for (int e = 0; e < V::N; e += 4) {
+        *reinterpret_cast<float4*>(pg + c * V::N + e) = make_float4(ag[i][e], ag[i][e + 1], ag[i][e + 2], ag[i][e + 3]);
+        *reinterpret_cast<float4*>(pb + c * V::N + e) = make_float4(ab[i][e], ab[i][e + 1], ab[i][e + 2], ab[i][e + 3]);
       }
-      o.store(dx + off + c * V::N);
     }
   }
 }
@@ -313,6 +367,41 @@ __global__ __launch_bounds__(256) void colsum_kernel(int rows, int N, const T* _
   }
 }
 
+// The same for N a multiple of 4 and many parts: a block takes 64 columns as 16 float4 lanes and
+// splits the parts 16 ways (thread = 16 * part group + column group), combining through LDS.
+__global__ __launch_bounds__(256) void fold_partials4_kernel(int parts, int N, const float* __restrict__ partial,
+                                                             float* __restrict__ out0, float* __restrict__ out1,
+                                                             int accumulate) {
+  __shared__ float4 red[16][16];
+  const int cg = threadIdx.x & 15, pgp = threadIdx.x >> 4;
+  const int n = blockIdx.x * 64 + cg * 4;
+  partial += (size_t)blockIdx.y * parts * N;
+  float* out = blockIdx.y ? out1 : out0;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (n < N) {
+#pragma unroll 4
+    for (int p = pgp; p < parts; p += 16) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)p * N + n);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  }
+  red[pgp][cg] = s;
+  __syncthreads();
+  if (pgp == 0 && n < N) {
+#pragma unroll
+    for (int g = 1; g < 16; g++) {
+      const float4 v = red[g][cg];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    float4* o = reinterpret_cast<float4*>(out + n);
+    if (accumulate) {
+      const float4 v = *o;
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    *o = s;
+  }
+}
+
 // out[n] (+)= sum_p partial[p * N + n], p < parts: 64 columns per block, 4 waves split the parts.
 // blockIdx.y = 1 folds a second stack of partials, stored right behind the first, into out1.
 __global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, const float* __restrict__ partial,
@@ -379,7 +468,8 @@ int fold_partials(int parts, size_t n, const float* partial, float* out, bool ac
 
 static int strips(int rows) { return max(1, min(CS_PARTS, (rows + 3) / 4)); }
 
-size_t ln_bwd_ws_bytes(int D) { return (size_t)2 * CS_PARTS * (size_t)D * sizeof(float); }
+static constexpr int LN_BWD_PARTS = 1024;  // workgroups (= partial rows) of the fused LayerNorm backward
+size_t ln_bwd_ws_bytes(int D) { return (size_t)2 * LN_BWD_PARTS * (size_t)D * sizeof(float); }
 size_t colsum_ws_bytes(int N) { return (size_t)CS_PARTS * (size_t)N * sizeof(float); }
 
 template <typename T>
@@ -388,26 +478,37 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
                     hipStream_t s) {
   constexpr int VN = Vec16<T>::N;
   const int nvec = D / VN;
+  const int gb = (D + 63) / 64;
   if (D % VN == 0 && nvec <= 256 * LN_MAXV) {
-    if (nvec <= 64 * LN_MAXV / 2)
-      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 64>), dim3((rows + 3) / 4), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd,
-                         gamma, dres, dx);
-    else if (nvec <= 128 * LN_MAXV / 2)
-      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 128>), dim3((rows + 1) / 2), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd,
-                         gamma, dres, dx);
+    // one pass: dx and, per workgroup, a partial row of dgamma and of dbeta
+    int parts;
+    auto grid = [&](int rpb) { return parts = min(LN_BWD_PARTS, (rows + rpb - 1) / rpb); };
+    // threads per row and vectors per thread: as few registers as the row length allows, so that
+    // several workgroups fit on a CU
+#define FAX_LN_BWD_FUSED(TPR, NV)                                                                                   \
+  hipLaunchKernelGGL((ln_bwd_fused_kernel<T, TPR, NV>), dim3(grid(LN_THREADS / TPR)), dim3(LN_THREADS), 0, s, rows, D, \
+                     dh, x, mu, rstd, gamma, dres, dx, partial)
+    if (nvec <= 64 * 2) FAX_LN_BWD_FUSED(64, 2);
+    else if (nvec <= 64 * 4) FAX_LN_BWD_FUSED(64, 4);
+    else if (nvec <= 256 * 2) FAX_LN_BWD_FUSED(256, 2);
+    else if (nvec <= 256 * 4) FAX_LN_BWD_FUSED(256, 4);
+    else FAX_LN_BWD_FUSED(256, LN_MAXV);
+#undef FAX_LN_BWD_FUSED
+    FAX_LAUNCH_CHECK("ln_bwd_fused");
+    if (D % 4 == 0 && ((reinterpret_cast<uintptr_t>(dgamma) | reinterpret_cast<uintptr_t>(dbeta)) & 15) == 0)
+      hipLaunchKernelGGL(fold_partials4_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
     else
-      hipLaunchKernelGGL((ln_bwd_dx_kernel<T, 256>), dim3(rows), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu, rstd, gamma,
-                         dres, dx);
-  } else {
-    hipLaunchKernelGGL((ln_bwd_dx_generic_kernel<T>), dim3((rows + 3) / 4), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu,
-                       rstd, gamma, dres, dx);
+      hipLaunchKernelGGL(fold_partials_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
+    FAX_LAUNCH_CHECK("ln_bwd_fold");
+    return FAX_OK;
   }
+  hipLaunchKernelGGL((ln_bwd_dx_generic_kernel<T>), dim3((rows + 3) / 4), dim3(LN_THREADS), 0, s, rows, D, dh, x, mu,
+                     rstd, gamma, dres, dx);
   FAX_LAUNCH_CHECK("ln_bwd_dx");
   const int parts = strips(rows);
   hipLaunchKernelGGL((colsum_kernel<T, 1>), dim3((D + 64 * VN - 1) / (64 * VN), parts), dim3(256), 0, s, rows, D, dh, D, x,
                      mu, rstd, partial);
   FAX_LAUNCH_CHECK("ln_bwd_dgamma_dbeta");
-  const int gb = (D + 63) / 64;
   hipLaunchKernelGGL(fold_partials_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
   FAX_LAUNCH_CHECK("ln_bwd_fold");
   return FAX_OK;
