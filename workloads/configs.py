@@ -93,7 +93,7 @@ CONFIGS = {
     "t1_16384": BlockShape(B=1, S=2048, D=16384, H=16, dh=128, F=8192, dtype="bf16", sigma_w=0.006, L=1),
     # The model of the per-phase timing figure (Fig. 4): "124M parameters", batch 32, sequence 2048.
     # The paper gives the size only; taken here: 12 layers, D = 768, 12 heads of 64, F = 3072 and a
-    # vocabulary of 50304 (124.5M parameters with the position table), everything else as cfg5.
+    # vocabulary of 50304 (125.3M parameters, 85.1M of them in the blocks), everything else as cfg5.
     "fig4_124m": ModelShape(BlockShape(B=32, S=2048, D=768, H=12, dh=64, F=3072, dtype="bf16",
                                        sigma_w=0.02, L=12), V=50304, S_max=2048),
 }
