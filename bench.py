@@ -99,6 +99,10 @@ def main():
         flops = cfg.flops_fwd_bwd(True)
         flops_full = cfg.flops_fwd_bwd(False)
         what = "fax_train_step: embedding + %d blocks + final LN + tied head + CE + backward + AdamW" % sh.L
+        ana = fax.fax_analyze(md)   # the static analyser's prediction for this model on one device, for comparison
+        analysis = {"predicted_ms": round(ana.ms_step, 2), "predicted_ms_gemm": round(ana.ms_gemm, 2),
+                    "predicted_ms_attention": round(ana.ms_attention, 2), "predicted_ms_bandwidth": round(ana.ms_bandwidth, 2),
+                    "device_bytes": int(ana.bytes_total)}
     else:
         ps, x, dy = make_stack_inputs(sh, seed=0)
         pd = [{k: up(p[k]) for k in PARAM_NAMES} for p in ps]
@@ -215,7 +219,8 @@ def main():
         "model_tflops": round(tflops, 2), "mfma_peak_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "model_tflops_unhalved_attention": round(flops_full / dt / 1e12, 2),
         "model_flop_per_step": flops,
-        "roofline": roof, "cpu_baseline": cpu, "phases": phases or None, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "phases": phases or None,
+        "analysis": analysis if is_model else None, "kernels": kernels,
     }
     print(json.dumps(out))
 

@@ -210,6 +210,52 @@ int fax_eval_step(const FaxModelDims* dims, const FaxModelTensors* params, const
                   const int32_t* labels, float* loss_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Static analysis of a model on a device mesh (host only: no GPU is touched, none is needed).
+ * Sec. 2.1 points out that memory requirements and latency estimates can be computed from
+ * the model's description before anything runs; Sec. 2.2 maps tensor axes onto the axes of a
+ * logical device mesh.  The mesh here has the paper's two axes: the batch dimension is split
+ * over `data`; heads, feed-forward columns (with them every large weight of a block, Sec. 3.2)
+ * and the rows of the token table over `tensor`.
+ *
+ * fax_analyze() takes the GLOBAL model (blk.B = global batch, blk.H = all heads, blk.F = full
+ * feed-forward width) and fills in what ONE device of the mesh holds and does per step:
+ *   local            the dims of its share (B/data, H/tensor, F/tensor, V/tensor when every
+ *                    rank's slice is a multiple of 128 rows, else V): the shapes every kernel
+ *                    of fax_train_step would see.
+ *                    Only the shapes: the reductions over the tensor axis (four [T, D] sums per
+ *                    block, the loss's row statistics) are not built.
+ *   params_*         parameter counts (LayerNorm tensors, the position table and the biases
+ *                    added after a reduction are replicated over the tensor axis)
+ *   bytes_*          device memory: fp32 master parameters, the two Adam moments, fp32
+ *                    gradients, the low-precision compute copy, saved activations and the
+ *                    rest of the workspace, exactly as the fax_*_layout / *_workspace_bytes
+ *                    calls size them
+ *   flop_*, hbm_bytes_step, launches
+ *                    algorithmic work of one training step on this device
+ *   ms_*             predicted time on one MI355X from the library's own launch plans: every
+ *                    GEMM priced by the tile/split plan it would run with, attention per
+ *                    score, bandwidth-bound kernels at a sustained HBM rate
+ *   bytes_*_axis     what one device would send per step over each mesh axis
+ * Errors: FAX_ERR_INVALID_ARG for NULL pointers, non-positive sizes, or a batch, head count or
+ * feed-forward width that the mesh does not divide (Sec. 3.2 requires it of the heads).
+ */
+typedef struct FaxMesh {
+  int32_t data, tensor;
+} FaxMesh;
+
+typedef struct FaxAnalysis {
+  FaxModelDims local;
+  double params_global, params_local;
+  double bytes_master, bytes_moments, bytes_grads, bytes_lowp, bytes_saved, bytes_workspace, bytes_total;
+  double flop_step, flop_step_unhalved, hbm_bytes_step;
+  int32_t launches;
+  double ms_gemm, ms_attention, ms_bandwidth, ms_step;
+  double bytes_tensor_axis, bytes_data_axis;
+} FaxAnalysis;
+
+int fax_analyze(const FaxModelDims* global_dims, const FaxMesh* mesh, FaxAnalysis* out);
+
+/*
  * Building blocks, exported so each kernel can be checked and timed alone.
  * All follow the conventions above; dtype is FAX_F32 or FAX_BF16.
  */

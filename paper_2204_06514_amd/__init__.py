@@ -65,6 +65,18 @@ class FaxModelTensors(C.Structure):
                 ("blocks", C.POINTER(FaxBlockTensors))]
 
 
+class FaxMesh(C.Structure):
+    _fields_ = [("data", C.c_int32), ("tensor", C.c_int32)]
+
+
+class FaxAnalysis(C.Structure):
+    _fields_ = [("local", FaxModelDims)] + [(n, C.c_double) for n in (
+        "params_global", "params_local", "bytes_master", "bytes_moments", "bytes_grads", "bytes_lowp", "bytes_saved",
+        "bytes_workspace", "bytes_total", "flop_step", "flop_step_unhalved", "hbm_bytes_step")] + [
+        ("launches", C.c_int32)] + [(n, C.c_double) for n in (
+            "ms_gemm", "ms_attention", "ms_bandwidth", "ms_step", "bytes_tensor_axis", "bytes_data_axis")]
+
+
 class FaxKernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_int32), ("unit", C.c_int32), ("ms", C.c_double),
                 ("work", C.c_double)]
@@ -100,6 +112,7 @@ def _load():
         "fax_attention_fwd": (i32, [i32] * 5 + [vp, vp, vp, i32, vp]),
         "fax_attention_bwd": (i32, [i32] * 5 + [vp, vp, vp, vp, vp, vp, i32, vp]),
         "fax_cross_entropy": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "fax_analyze": (i32, [P(FaxModelDims), P(FaxMesh), P(FaxAnalysis)]),
         "fax_timing_enable": (i32, [i32]),
         "fax_timing_report": (i32, [P(FaxKernelTime), i32, P(i32)]),
     }
@@ -203,6 +216,13 @@ def fax_eval_workspace_bytes(mdims):
     out = C.c_size_t()
     _check(_lib.fax_eval_workspace_bytes(C.byref(mdims), C.byref(out)))
     return out.value
+
+
+def fax_analyze(mdims, data=1, tensor=1):
+    """mdims: the GLOBAL model; returns the FaxAnalysis of one device of a data x tensor mesh."""
+    out = FaxAnalysis()
+    _check(_lib.fax_analyze(C.byref(mdims), C.byref(FaxMesh(data, tensor)), C.byref(out)))
+    return out
 
 
 def fax_eval_step(mdims, params, tokens, labels, loss_out, ws, ws_bytes, stream=None):

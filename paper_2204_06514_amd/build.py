@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfax.so")
 
 SOURCES = ["fax_api.hip", "kernels_norm.hip", "kernels_gemm_simt.hip", "kernels_gemm_mfma.hip",
-           "kernels_attn_simt.hip", "kernels_attn_mfma.hip", "kernels_loss_opt.hip"]
+           "kernels_attn_simt.hip", "kernels_attn_mfma.hip", "kernels_loss_opt.hip", "analyze.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -575,6 +575,27 @@ size_t gemm_split_ws_bytes(int M, int N, int K) {
   return split_ws_bytes_1(M, N, K);  // a column strip keeps the leading dimension of C: no split there
 }
 
+static double time_estimate_1(int M, int N, int K, bool f32_out) {
+  const GemmSplitPlan plan = f32_out ? gemm_split_plan(M, N, K) : GemmSplitPlan{pick_tile_mn(M, N), 1};
+  if (plan.tile == 0 || K % GK) return 2.0 * M * N * K / 15.0e6;  // the scalar kernel: about 15 TFLOP/s
+  const int s = plan.splits, nkt = K / GK;
+  const double t_slab = plan.tile == 256 ? 1.55 : 0.66;
+  const double t_epi = plan.tile == 256 ? (f32_out ? 8.0 : 7.0) : 3.0;
+  const long long tiles = (long long)(M / plan.tile) * (N / plan.tile);
+  const long long rounds = (tiles * s + kCUs - 1) / kCUs;
+  double t = 3.0 + rounds * ((nkt + s - 1) / s * t_slab + t_epi);
+  if (s > 1) t += 10.0 + (2.0 * s + 1.0) * M * N * 4.0 / 3.0e6;
+  return t;
+}
+
+double gemm_time_estimate_us(int M, int N, int K, bool f32_out) {
+  switch (tail_dim(M, N)) {
+    case 1: return time_estimate_1(M - 128, N, K, f32_out) + time_estimate_1(128, N, K, f32_out);
+    case 2: return time_estimate_1(M, N - 128, K, f32_out) + time_estimate_1(M, 128, K, f32_out);
+  }
+  return time_estimate_1(M, N, K, f32_out);
+}
+
 static int pick_tile(const GemmArgs& g) { return pick_tile_mn(g.M, g.N); }
 
 bool gemm_mfma_supported(const GemmArgs& g) {
