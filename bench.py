@@ -123,6 +123,8 @@ def main():
             vo = [{k: torch.zeros_like(t) for k, t in p.items()} for p in master]
         pt = [fax.block_tensors(p) for p in pd]
         gt = [fax.block_tensors(g) for g in gd]
+        if with_adam:
+            mt, mot, vot = ([fax.block_tensors(t) for t in ts] for ts in (master, mo, vo))
         state = {"t": 0}
 
         def step():
@@ -133,12 +135,10 @@ def main():
             if with_adam:
                 state["t"] += 1
                 for l in range(sh.L):
-                    for k in PARAM_NAMES:
-                        fax.fax_adamw_step(master[l][k], mo[l][k], vo[l][k], gd[l][k], pd[l][k], master[l][k].numel(),
-                                           hp, state["t"])
+                    fax.fax_adamw_block_step(dims, mt[l], mot[l], vot[l], gt[l], pt[l], hp, state["t"])
         flops = sh.L * sh.block_flops_fwd_bwd(True)
         flops_full = sh.L * sh.block_flops_fwd_bwd(False)
-        what = "%d x (fax_block_fwd + fax_block_bwd)%s" % (sh.L, " + fax_adamw_step on every tensor" if with_adam else "")
+        what = "%d x (fax_block_fwd + fax_block_bwd)%s" % (sh.L, " + fax_adamw_block_step per block (AdamW on every tensor)" if with_adam else "")
 
     if args.calib_copy:
         # an elementwise fp32 -> bf16 copy: reads exactly 2^28 bytes, writes exactly 2^27

@@ -182,6 +182,13 @@ int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const
 int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp, size_t n,
                    const FaxAdamW* hp, int step, void* stream);
 
+/* The same update on the twelve tensors of a block in one launch (most of them are a few KB: a
+ * launch each costs more than their update).  Tensor sizes follow from dims.  lowp: the bf16
+ * compute copies to refresh, or NULL (fp32 models: the master tensors are the parameters). */
+int fax_adamw_block_step(const FaxBlockDims* dims, const FaxBlockTensors* master, const FaxBlockTensors* m,
+                         const FaxBlockTensors* v, const FaxBlockTensors* grads, const FaxBlockTensors* lowp,
+                         const FaxAdamW* hp, int step, void* stream);
+
 /*
  * One training step of the full model (forward, loss, backward, update: Fig. 4 + Table 1):
  *   x0 = tok_emb[tokens] + pos_emb[s];  L blocks;  hf = LN(x_L; lnf);  logits = hf tok_emb^T;

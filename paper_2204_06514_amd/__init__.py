@@ -103,6 +103,7 @@ def _load():
         "fax_block_bwd": (i32, [P(FaxBlockDims), P(FaxBlockTensors), vp, vp, vp, vp, P(FaxBlockTensors), i32,
                                 vp, sz, vp]),
         "fax_adamw_step": (i32, [vp, vp, vp, vp, vp, sz, P(FaxAdamW), i32, vp]),
+        "fax_adamw_block_step": (i32, [P(FaxBlockDims)] + [P(FaxBlockTensors)] * 5 + [P(FaxAdamW), i32, vp]),
         "fax_train_step": (i32, [P(FaxModelDims)] + [P(FaxModelTensors)] * 5 + [vp, vp, P(FaxAdamW), i32, vp, vp,
                                                                                   sz, vp]),
         "fax_gemm": (i32, [i32] * 6 + [vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, i32, i32, vp]),
@@ -244,6 +245,12 @@ def fax_block_bwd(dims, params, x, dy, saved, dx, grads, accumulate, ws, ws_byte
 def fax_adamw_step(master, m, v, grad, lowp, n, hp, step, stream=None):
     _check(_lib.fax_adamw_step(_ptr(master), _ptr(m), _ptr(v), _ptr(grad), _ptr(lowp), n, C.byref(hp), step,
                                _stream(stream)))
+
+
+def fax_adamw_block_step(dims, master, m, v, grads, lowp, hp, step, stream=None):
+    """master, m, v, grads, lowp: FaxBlockTensors (see block_tensors); lowp may be None."""
+    _check(_lib.fax_adamw_block_step(C.byref(dims), C.byref(master), C.byref(m), C.byref(v), C.byref(grads),
+                                     C.byref(lowp) if lowp is not None else None, C.byref(hp), step, _stream(stream)))
 
 
 def fax_train_step(mdims, params, master, m, v, grads, tokens, labels, hp, step, loss_out, ws, ws_bytes, stream=None):

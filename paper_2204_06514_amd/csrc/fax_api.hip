@@ -488,6 +488,34 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
   return adamw((float*)master, (float*)m, (float*)v, (const float*)grad, lowp, n, *hp, step, (hipStream_t)stream);
 }
 
+int fax_adamw_block_step(const FaxBlockDims* dims, const FaxBlockTensors* master, const FaxBlockTensors* m,
+                         const FaxBlockTensors* v, const FaxBlockTensors* grads, const FaxBlockTensors* lowp,
+                         const FaxAdamW* hp, int step, void* stream) {
+  FAX_TRY(check_dims(dims));
+  FAX_TRY(check_tensors(master, "master"));
+  FAX_TRY(check_tensors(m, "m"));
+  FAX_TRY(check_tensors(v, "v"));
+  FAX_TRY(check_tensors(grads, "grads"));
+  if (lowp) FAX_TRY(check_tensors(lowp, "lowp"));
+  if (!hp) { set_error("hp is NULL"); return FAX_ERR_INVALID_ARG; }
+  if (step < 1) { set_error("step must be >= 1, got %d", step); return FAX_ERR_INVALID_ARG; }
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
+    set_error("betas must lie in [0, 1)");
+    return FAX_ERR_INVALID_ARG;
+  }
+  size_t n[12];
+  tensor_counts(*dims, n);
+  void* const* Ms = (void* const*)tensor_list(master);
+  void* const* Mo = (void* const*)tensor_list(m);
+  void* const* Vo = (void* const*)tensor_list(v);
+  void* const* G = (void* const*)tensor_list(grads);
+  void* const* P = lowp ? (void* const*)tensor_list(lowp) : nullptr;
+  AdamWQueue q(*hp, step, (hipStream_t)stream);
+  for (int i = 0; i < 12; i++)
+    FAX_TRY(q.add((float*)Ms[i], (float*)Mo[i], (float*)Vo[i], (const float*)G[i], P ? P[i] : nullptr, n[i]));
+  return q.flush();
+}
+
 // Evaluation: two activation buffers that take turns, one block's worth of saved tensors that every
 // layer overwrites, the final LayerNorm, the logits, per-row losses.
 struct EvalWs {
@@ -655,8 +683,9 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   Timed phase_("phase_update", WORK_BYTE, 28.0 * ((double)V * D + (double)dims->S_max * D), s);
 
   const bool lowp = d.dtype == FAX_BF16;
+  AdamWQueue q(*hp, step, s);
   auto upd = [&](void* P, void* Mst, void* Mo, void* Vo, const void* G, size_t n) {
-    return adamw((float*)Mst, (float*)Mo, (float*)Vo, (const float*)G, lowp ? P : nullptr, n, *hp, step, s);
+    return q.add((float*)Mst, (float*)Mo, (float*)Vo, (const float*)G, lowp ? P : nullptr, n);
   };
   FAX_TRY(upd(params->tok_emb, master->tok_emb, m->tok_emb, v->tok_emb, grads->tok_emb, (size_t)V * D));
   FAX_TRY(upd(params->pos_emb, master->pos_emb, m->pos_emb, v->pos_emb, grads->pos_emb, (size_t)dims->S_max * D));
@@ -672,7 +701,7 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
     void* const* G = (void* const*)tensor_list(&grads->blocks[l]);
     for (int i = 0; i < 12; i++) FAX_TRY(upd(P[i], Ms[i], Mo[i], Vo[i], G[i], n[i]));
   }
-  return FAX_OK;
+  return q.flush();
 }
 
 int fax_timing_enable(int on) {

@@ -112,6 +112,33 @@ int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void*
 // g_tok[tokens[b,s]] += dx0[b,s] (fp32 atomics); g_pos[s] (+)= sum_b dx0[b,s]; rows of g_pos beyond S untouched.
 int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
               bool accumulate_pos, hipStream_t s);
+// Up to ADAM_BATCH tensors per launch.  add() queues a tensor (launching what is queued when the
+// batch is full), flush() launches the rest; nothing is kept beyond flush().
+constexpr int ADAM_BATCH = 16;
+constexpr int ADAM_CHUNK = 4096;  // elements per workgroup
+struct AdamWBatch {
+  float* p[ADAM_BATCH];
+  float* m[ADAM_BATCH];
+  float* v[ADAM_BATCH];
+  const float* g[ADAM_BATCH];
+  bf16_t* lowp[ADAM_BATCH];
+  size_t n[ADAM_BATCH];
+  unsigned first[ADAM_BATCH + 1];  // first workgroup of each tensor; first[count] = grid size
+  int count;
+};
+struct AdamWQueue {
+  AdamWQueue(const FaxAdamW& hp_, int step_, hipStream_t s_) : hp(hp_), step(step_), s(s_) {
+    b.count = 0;
+    b.first[0] = 0;
+  }
+  int add(float* master, float* m, float* v, const float* grad, void* lowp, size_t n);
+  int flush();
+  AdamWBatch b;
+  FaxAdamW hp;
+  int step;
+  hipStream_t s;
+  double bytes = 0;
+};
 int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
           hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);

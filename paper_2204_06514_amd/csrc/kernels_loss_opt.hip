@@ -240,10 +240,66 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict_
   }
 }
 
+static AdamScalars adam_scalars(const FaxAdamW& hp, int step);
+
 int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
           hipStream_t s) {
   if (n == 0) return FAX_OK;
   Timed t_("adamw", WORK_BYTE, (lowp ? 30.0 : 28.0) * (double)n, s);
+  const AdamScalars a = adam_scalars(hp, step);
+  size_t blocks = (n / 4 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, grad, (bf16_t*)lowp, a);
+  FAX_LAUNCH_CHECK("adamw");
+  return FAX_OK;
+}
+
+// Several tensors per launch: a model has a dozen tensors per layer, most of them a few KB, and a
+// launch per tensor costs more than their update.  Workgroup w works on chunk w - first[t] (4096
+// elements) of the tensor t whose range of workgroups contains w.
+__global__ __launch_bounds__(256) void adamw_multi_kernel(AdamWBatch b, AdamScalars a) {
+  int t = 0;
+  while (t + 1 < b.count && blockIdx.x >= b.first[t + 1]) t++;  // uniform over the workgroup
+  const size_t n = b.n[t], nvec = n / 4;
+  float* const p = b.p[t];
+  float* const m = b.m[t];
+  float* const v = b.v[t];
+  const float* const g = b.g[t];
+  bf16_t* const lowp = b.lowp[t];
+  const size_t chunk = blockIdx.x - b.first[t];
+#pragma unroll
+  for (int k = 0; k < ADAM_CHUNK / 1024; k++) {
+    const size_t i = chunk * (ADAM_CHUNK / 4) + k * 256 + threadIdx.x;
+    if (i < nvec) {
+      float4 pv = reinterpret_cast<float4*>(p)[i], mv = reinterpret_cast<float4*>(m)[i];
+      float4 vv = reinterpret_cast<float4*>(v)[i];
+      const float4 gv = reinterpret_cast<const float4*>(g)[i];
+      adam_one(gv.x, pv.x, mv.x, vv.x, a);
+      adam_one(gv.y, pv.y, mv.y, vv.y, a);
+      adam_one(gv.z, pv.z, mv.z, vv.z, a);
+      adam_one(gv.w, pv.w, mv.w, vv.w, a);
+      reinterpret_cast<float4*>(p)[i] = pv;
+      reinterpret_cast<float4*>(m)[i] = mv;
+      reinterpret_cast<float4*>(v)[i] = vv;
+      if (lowp) {
+        union { bf16_t h[4]; uint2 u; } pk;
+        pk.h[0] = (bf16_t)pv.x; pk.h[1] = (bf16_t)pv.y; pk.h[2] = (bf16_t)pv.z; pk.h[3] = (bf16_t)pv.w;
+        reinterpret_cast<uint2*>(lowp)[i] = pk.u;
+      }
+    }
+  }
+  // ragged tail (at most three elements), by the tensor's last workgroup
+  const size_t i = nvec * 4 + threadIdx.x;
+  if (blockIdx.x + 1 == b.first[t + 1] && i < n) {
+    float pp = p[i], mm = m[i], vv = v[i];
+    adam_one(g[i], pp, mm, vv, a);
+    p[i] = pp; m[i] = mm; v[i] = vv;
+    if (lowp) lowp[i] = (bf16_t)pp;
+  }
+}
+
+static AdamScalars adam_scalars(const FaxAdamW& hp, int step) {
   AdamScalars a;
   a.b1 = (float)hp.beta1; a.b2 = (float)hp.beta2;
   a.one_m_b1 = (float)(1.0 - hp.beta1); a.one_m_b2 = (float)(1.0 - hp.beta2);
@@ -251,11 +307,34 @@ int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size
   a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp.beta2, (double)step)));
   a.lr = (float)hp.lr; a.eps = (float)hp.eps;
   a.decay = (float)(1.0 - hp.lr * hp.wd);
-  size_t blocks = (n / 4 + 255) / 256;
-  if (blocks < 1) blocks = 1;
-  if (blocks > 256 * 16) blocks = 256 * 16;
-  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, grad, (bf16_t*)lowp, a);
-  FAX_LAUNCH_CHECK("adamw");
+  return a;
+}
+
+int AdamWQueue::add(float* master, float* m, float* v, const float* grad, void* lowp, size_t n) {
+  if (n == 0) return FAX_OK;
+  const size_t chunks = (n + ADAM_CHUNK - 1) / ADAM_CHUNK;
+  if (chunks > 0x7fffffffu) {
+    set_error("adamw: tensor of %zu elements", n);
+    return FAX_ERR_UNSUPPORTED;
+  }
+  if (b.count == ADAM_BATCH || (size_t)b.first[b.count] + chunks > 0x7fffffffu) FAX_TRY(flush());
+  const int t = b.count++;
+  b.p[t] = master; b.m[t] = m; b.v[t] = v; b.g[t] = grad; b.lowp[t] = (bf16_t*)lowp; b.n[t] = n;
+  b.first[t + 1] = b.first[t] + (unsigned)chunks;
+  bytes += (lowp ? 30.0 : 28.0) * (double)n;
+  return FAX_OK;
+}
+
+int AdamWQueue::flush() {
+  if (b.count == 0) return FAX_OK;
+  {
+    Timed t_("adamw", WORK_BYTE, bytes, s);
+    hipLaunchKernelGGL(adamw_multi_kernel, dim3(b.first[b.count]), dim3(256), 0, s, b, adam_scalars(hp, step));
+    FAX_LAUNCH_CHECK("adamw");
+  }
+  b.count = 0;
+  b.first[0] = 0;
+  bytes = 0;
   return FAX_OK;
 }
 

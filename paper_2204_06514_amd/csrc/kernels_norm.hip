@@ -482,7 +482,9 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
   if (D % VN == 0 && nvec <= 256 * LN_MAXV) {
     // one pass: dx and, per workgroup, a partial row of dgamma and of dbeta
     int parts;
-    auto grid = [&](int rpb) { return parts = min(LN_BWD_PARTS, (rows + rpb - 1) / rpb); };
+    // at least eight row blocks per workgroup: each workgroup writes two partial rows, which would
+    // otherwise rival the traffic of the rows themselves when there are few tokens
+    auto grid = [&](int rpb) { return parts = max(1, min(LN_BWD_PARTS, (rows + 8 * rpb - 1) / (8 * rpb))); };
     // threads per row and vectors per thread: as few registers as the row length allows, so that
     // several workgroups fit on a CU
 #define FAX_LN_BWD_FUSED(TPR, NV)                                                                                   \

@@ -45,10 +45,10 @@ def test_cfg2_two_layer_stack_with_adamw_full_size():
         fax.fax_block_bwd(dims, pd[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gd[l], 0, ws, wsb)
     master = [{k: t.float().clone() for k, t in p.items()} for p in pd]
     hp = fax.FaxAdamW(**ADAMW_DEFAULT)
-    for l in range(sh.L):
-        for k in PARAM_NAMES:
-            m = torch.zeros_like(master[l][k]); v = torch.zeros_like(master[l][k])
-            fax.fax_adamw_step(master[l][k], m, v, gd[l][k], pd[l][k], master[l][k].numel(), hp, 1)
+    for l in range(sh.L):   # one launch per block
+        m = {k: torch.zeros_like(t) for k, t in master[l].items()}
+        v = {k: torch.zeros_like(t) for k, t in master[l].items()}
+        fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (master[l], m, v, gd[l], pd[l])), hp, 1)
     torch.cuda.synchronize()
     y, caches = orc.stack_fwd(x, ps, sh.H, sh.dh)
     dx, g = orc.stack_bwd(dy, caches, ps)

@@ -201,6 +201,39 @@ def test_adamw_three_steps_and_bf16_copy(n):
     assert rel_max(to_np(pd), p0 * (1 - 1e-5) - 1e-3 * g / (np.abs(g) + 1e-8)) <= 1e-6
 
 
+def test_adamw_block_step_updates_all_twelve_tensors_like_the_single_tensor_call():
+    """Ragged tensor sizes (not multiples of 4, some below and some above one workgroup's chunk)."""
+    B, S, D, H, dh, F = 1, 8, 73, 3, 7, 1501
+    dims = fax.block_dims(B, S, D, H, dh, F, fax.FAX_BF16, fax.FAX_GELU_TANH, 1e-5, 0)
+    shapes = {"ln1_g": D, "ln1_b": D, "wqkv": D * 3 * H * dh, "bqkv": 3 * H * dh, "wo": H * dh * D, "bo": D,
+              "ln2_g": D, "ln2_b": D, "w1": D * F, "b1": F, "w2": F * D, "b2": D}
+    assert list(shapes) == list(fax.TENSOR_NAMES)
+    rng = np.random.default_rng(5)
+    hp = fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.01)
+    p = {k: rng.standard_normal(n).astype(np.float32) for k, n in shapes.items()}
+    m = {k: (0.1 * rng.standard_normal(n)).astype(np.float32) for k, n in shapes.items()}
+    v = {k: (0.01 * rng.random(n)).astype(np.float32) for k, n in shapes.items()}
+    g = {k: rng.standard_normal(n).astype(np.float32) for k, n in shapes.items()}
+    dev = lambda d: {k: torch.from_numpy(a.copy()).to(DEV) for k, a in d.items()}
+    pd, md, vd, gd = dev(p), dev(m), dev(v), dev(g)
+    low = {k: torch.zeros(n, dtype=torch.bfloat16, device=DEV) for k, n in shapes.items()}
+    fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, md, vd, gd, low)), hp, 3)
+    p1, m1, v1 = dev(p), dev(m), dev(v)
+    for k, n in shapes.items():
+        ref_p, ref_m, ref_v = orc.adamw(p[k].astype(np.float64), m[k].astype(np.float64), v[k].astype(np.float64),
+                                        g[k].astype(np.float64), 1e-3, 0.9, 0.999, 1e-8, 0.01, 3)
+        assert rel_max(to_np(pd[k]), ref_p) <= 1e-6 and rel_max(to_np(md[k]), ref_m) <= 1e-6, k
+        assert rel_max(to_np(vd[k]), ref_v) <= 1e-6, k
+        assert torch.equal(low[k], pd[k].to(torch.bfloat16)), k
+        # and bit for bit what the one-tensor entry point computes
+        fax.fax_adamw_step(p1[k], m1[k], v1[k], gd[k], None, n, hp, 3)
+        assert torch.equal(p1[k], pd[k]) and torch.equal(m1[k], md[k]) and torch.equal(v1[k], vd[k]), k
+    # without the low-precision copies
+    fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, md, vd, gd)), None, hp, 4)
+    fax.fax_adamw_step(p1["w1"], m1["w1"], v1["w1"], gd["w1"], None, shapes["w1"], hp, 4)
+    assert torch.equal(p1["w1"], pd["w1"])
+
+
 # ------------------------------------------------------------------------- per-kernel timing
 def test_timing_report_names_kernels_and_counts_their_work():
     """bench.py's roofline entry rests on this: HIP events around each kernel family on the launch stream."""
