@@ -638,7 +638,12 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
     n_cu = v > 0 ? v : 256;
   }
   const int items = tiles_m * tiles_n * (e.splits > 1 ? e.splits : 1);
-  const int grid = items < n_cu ? items : n_cu;  // persistent: one workgroup per CU
+  // Persistent: one workgroup per CU.  A 128^2 workgroup needs 80 KB of LDS and under 256 registers,
+  // so two fit on a CU; they share its LDS bandwidth, which bounds that kernel, and gain little
+  // (measured: +-0.4 % with many tiles) except when that saves a second round for a few left-over
+  // tiles (320 tiles: -4 % on the whole step).
+  const int slots = (BT == 128 && items <= 2 * n_cu) ? 2 * n_cu : n_cu;
+  const int grid = items < slots ? items : slots;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.M, g.N, g.K, (const bf16_t*)g.A, g.lda,
                      (const bf16_t*)g.B, g.ldb, e, tiles_m, tiles_n);
   FAX_LAUNCH_CHECK("gemm_mfma");
