@@ -140,14 +140,18 @@ __device__ __forceinline__ void store_rows(bf16_t* __restrict__ dst, const f32x1
     }
 }
 
+// Segment i of this wave's share of a 64 x DH tile (see tile_dma above), as one load instruction:
+// wave-uniform tile address in scalar registers plus a per-lane byte offset that depends only on
+// the lane, the segment and the row stride, so the compiler computes it once per kernel and a load
+// costs no vector arithmetic.  `wave` must be wave-uniform (readfirstlane).
 template <int DH>
-__device__ __forceinline__ void tile_dma_seg(unsigned lds, const bf16_t* __restrict__ src, size_t ld, int i) {
+__device__ __forceinline__ void tile_dma_seg(unsigned lds, const bf16_t* __restrict__ src, size_t ld, int wave, int i) {
   constexpr int NCH = DH / 8, RPI = 64 / NCH;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
   const int seg = wave * (DH / 32) + i;
   const int row = seg * RPI + lane / NCH;
   const int chunk = (lane % NCH) ^ swz<DH>(row);
-  lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
+  lds_dma16(src, (unsigned)(((size_t)row * ld + chunk * 8) * sizeof(bf16_t)), lds + seg * 1024u);
 }
 
 // Workgroup -> (pair of 128-row tiles, batch-head) for the three kernels.  Under the causal mask
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_fwd_phased_mfma_kernel(int S, int H,
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
   const float scale = rsqrtf((float)DH);
   const float c = scale * LOG2E;
   const unsigned sm = lds_addr(smem);
@@ -223,8 +227,8 @@ __global__ __launch_bounds__(256) void attn_fwd_phased_mfma_kernel(int S, int H,
     const int n_kv = 2 * (qt + 1);
     auto tile_load = [&](int j0, int buf, int i) {
       const unsigned st = sm + buf * 2 * TB;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
-      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
     };
     bf16x8 fr[LEAD], fc[LEAD];
     // One 64-key tile.  MASK: the tile may reach past the wave's first query.
@@ -362,7 +366,7 @@ __global__ __launch_bounds__(256) void attn_fwd_skewed_mfma_kernel(int S, int H,
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
   const float scale = rsqrtf((float)DH);
   const float c = scale * LOG2E;
   const unsigned sm = lds_addr(smem);
@@ -387,8 +391,8 @@ __global__ __launch_bounds__(256) void attn_fwd_skewed_mfma_kernel(int S, int H,
     const int n_kv = 2 * (qt + 1), n_half = 2 * n_kv;
     auto tile_load = [&](int j0, int buf, int i) {
       const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
-      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
     };
     auto stage = [&](int t) { return smem + (min(t, n_kv - 1) % NBUF) * STAGE; };  // past the end: the last tile again
     auto row_frag = [&](const char* st, int jt, int i) { return frag_rows<DH>(st, jt * 32, i, lane); };
@@ -532,7 +536,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
   const int Hd = H * DH;
   const size_t ld = 3 * (size_t)Hd;
   const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
   const float scale = rsqrtf((float)DH);
   const float c = scale * LOG2E;
   const unsigned sm = lds_addr(smem);
@@ -573,8 +577,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
     const int n_kv = 2 * (qt + 1), n_half = 2 * n_kv;
     auto tile_load = [&](int j0, int buf, int i) {
       const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, i);
-      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, i - NSEG);
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
     };
     auto stage = [&](int t) { return smem + (min(t, n_kv - 1) % NBUF) * STAGE; };  // past the end: the last tile again
     auto row_frag = [&](const char* st, int jt, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, jt * 32, i / 2, lane); };
@@ -737,8 +741,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, in
     // segments of Q (i < NSEG), of dO (i < 2 NSEG), and its 16 lse and 16 delta values.
     auto tile_load = [&](int i0, int buf, int i) {
       const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, i);
-      else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, i - NSEG);
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, wave, i);
+      else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, wave, i - NSEG);
       else lds_dma4(((lane & 16) ? drow : lrow) + i0 + wave * 16 + (lane & 15), st + LD_OFF + wave * 256);
     };
     auto stage = [&](int t) { return smem + (min(t, n_q - 1) % NBUF) * STAGE; };  // past the end: the last tile again
