@@ -44,6 +44,7 @@ using F_ = std::false_type;
 
 static constexpr float LOG2E = 1.4426950408889634f;
 static constexpr int TR = 64;  // rows per LDS tile
+static constexpr float MAX_LAG = 8.f;  // forward: octaves the running maximum may rise above the exponent's reference point
 
 template <int DH>
 __device__ __forceinline__ int swz(int row) {
@@ -276,8 +277,22 @@ __global__ __launch_bounds__(256) void attn_fwd_phased_mfma_kernel(int S, int H,
 #pragma unroll
         for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[jt][v]);
       mx = max32(mx);
+      // The reference point of the exponentials, m, follows the running maximum lazily: it moves
+      // (and the accumulators are rescaled) only when some query's maximum has risen more than
+      // MAX_LAG octaves above it, which after the first few tiles is rare.  Probabilities are then
+      // at most 2^MAX_LAG instead of 1; numerator, denominator and lse all use the same m, so
+      // the result is the same softmax.
       const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and comes in the first tile
-      const float mc = mn * c;
+      if (__builtin_amdgcn_ballot_w64((mn - m) * c > MAX_LAG) != 0) {
+        const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
+        l *= corr;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
+        m = mn;
+      }
+      const float mc = m * c;
       float rs = 0.f;
       bf16x8 pb[2][2];
 #pragma unroll
@@ -289,18 +304,7 @@ __global__ __launch_bounds__(256) void attn_fwd_phased_mfma_kernel(int S, int H,
           pb[jt][v >> 3][v & 7] = (__bf16)p;
         }
       rs = sum32(rs);
-      // The running maximum settles after the first few tiles; rescale the accumulators only
-      // when some query of the wave actually moved it.
-      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {
-        const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
-        l *= corr;
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
-      }
       l += rs;
-      m = mn;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < N; i++) {
@@ -425,19 +429,18 @@ __global__ __launch_bounds__(256) void attn_fwd_skewed_mfma_kernel(int S, int H,
         __builtin_amdgcn_sched_barrier(0);
       }
       mx = max32(mx);
+      // lazy reference point, as in the kernel above
       const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and comes in the first half
-      const float mc = mn * c;
-      // The running maximum settles after the first few halves; rescale the accumulators only
-      // when some query of the wave actually moved it.
-      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {
+      if (__builtin_amdgcn_ballot_w64((mn - m) * c > MAX_LAG) != 0) {
         const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
         l *= corr;
 #pragma unroll
         for (int dt = 0; dt < DT; dt++)
 #pragma unroll
           for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
+        m = mn;
       }
-      m = mn;
+      const float mc = m * c;
       if (JT == 0) {
         // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
         // half u - 1, the last reader of tile t - 1
