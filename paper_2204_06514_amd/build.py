@@ -30,9 +30,15 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
+# Per-file additions.  The attention kernels run their softmax arithmetic on MFMA results: with the
+# accumulators in AGPRs (the compiler's default under register pressure) every score costs an extra
+# copy instruction on the vector unit, which bounds those kernels; the VGPR form avoids most copies.
+EXTRA = {"kernels_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc()] + FLAGS + EXTRA.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     log = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
