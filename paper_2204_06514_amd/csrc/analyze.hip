@@ -20,8 +20,8 @@ struct AttnCost {
   double fwd, dq, dkv;
 };
 static AttnCost attn_cost(int dh, int S, int dtype) {
-  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 128) return {1.10, 1.21, 1.55};
-  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 64) return {0.63, 0.60, 0.77};
+  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 128) return {0.78, 1.10, 1.48};
+  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 64) return {0.39, 0.49, 0.89};
   const double c = 0.25 * dh;  // the scalar kernels: a few TFLOP/s
   return {c, 2 * c, 2 * c};
 }
