@@ -83,7 +83,10 @@ def test_gemm_auto_path_falls_back_on_ragged_shapes():
 # ------------------------------------------------------------------------- LayerNorm
 @pytest.mark.parametrize("dtype,rows,D", [("f32", 128, 128), ("f32", 37, 100), ("f32", 9, 4096), ("bf16", 300, 1024),
                                           ("bf16", 129, 4096), ("bf16", 33, 12288), ("bf16", 21, 1000),
-                                          ("bf16", 17, 20000)])
+                                          ("bf16", 17, 20000),
+                                          # every lanes-per-row x vectors-per-thread form of the one-pass backward,
+                                          # and a workgroup that walks over many row blocks with a ragged last one
+                                          ("bf16", 70, 2048), ("f32", 50, 768), ("bf16", 20, 8192), ("bf16", 5001, 768)])
 def test_layernorm_forward_backward(dtype, rows, D):
     rng = np.random.default_rng(rows + D)
     x = _store(rng.standard_normal((rows, D)) * 2 + 0.5, dtype)
