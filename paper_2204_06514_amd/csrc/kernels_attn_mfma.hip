@@ -76,24 +76,38 @@ __device__ __forceinline__ void tile_dma(unsigned lds, const bf16_t* __restrict_
   }
 }
 
-// A operand, rows rb..rb+31 of the tile, contraction over the tile's columns (k-step ks).
+// The two fragment readers below are called with compile-time tile coordinates.  Their addresses
+// are written as (one per-lane value, the same for every call) XOR (a constant) + (a constant):
+// the swizzle only involves row bits 0..3 and chunk bits, which the tile coordinates (multiples of
+// 16 rows, whole k-steps, 32-column blocks) enter without carries.  Spelled as tile_off(row, chunk)
+// per call, each coordinate pair is a separate loop-invariant vector value to the compiler: some
+// fifty registers per kernel, more than the register budget of two waves per SIMD leaves.
+
+// A operand, rows rb..rb+31 of the tile (rb a multiple of 16), contraction over the tile's columns
+// (k-step ks).
 template <int DH>
 __device__ __forceinline__ bf16x8 frag_rows(const char* lds, int rb, int ks, int lane) {
-  const int row = rb + (lane & 31);
-  const uint4 v = *reinterpret_cast<const uint4*>(lds + tile_off<DH>(row, ks * 2 + (lane >> 5)));
+  const int l31 = lane & 31;
+  const unsigned lane_part = l31 * (DH * 2) + (((lane >> 5) ^ swz<DH>(l31)) << 4);  // tile_off(l31, lane >> 5)
+  const unsigned off = (lane_part ^ (unsigned)(ks << 5)) + (unsigned)(rb * (DH * 2));  // tile_off(rb + l31, 2 ks + (lane >> 5))
+  const uint4 v = *reinterpret_cast<const uint4*>(lds + off);
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// A operand = transpose of the tile: output rows are tile columns cb..cb+31, contraction over
-// tile rows r0 + {0..3, 8..11} + 4 g (the k-slot order described in the header).
+// A operand = transpose of the tile: output rows are tile columns cb..cb+31 (cb a multiple of 32),
+// contraction over tile rows r0 + {0..3, 8..11} + 4 g (r0 a multiple of 16; the k-slot order
+// described in the header).
 template <int DH>
 __device__ __forceinline__ bf16x8 frag_cols(const char* lds, int cb, int r0, int lane) {
   const int blk = lane >> 4, i = lane & 15;
-  const int row = r0 + (blk >> 1) * 4 + (i >> 2);
-  const int col = cb + (blk & 1) * 16 + (i & 3) * 4;
+  const int rl = (blk >> 1) * 4 + (i >> 2);        // row within the group of 16
+  const int cl = (blk & 1) * 16 + (i & 3) * 4;     // column within the block of 32
+  const unsigned lane_part = rl * (DH * 2) + (((cl >> 3) ^ swz<DH>(rl)) << 4) + ((cl >> 2) & 1) * 8;
+  const unsigned x = lane_part ^ (unsigned)((cb >> 3) << 4);
   typedef __attribute__((address_space(3))) short4v lds_s4;
-  const char* p0 = lds + tile_off<DH>(row, col >> 3) + ((col >> 2) & 1) * 8;
-  const char* p1 = lds + tile_off<DH>(row + 8, col >> 3) + ((col >> 2) & 1) * 8;
+  const char* p0 = lds + x + (unsigned)(r0 * (DH * 2));
+  // eight rows further down: row bit 3 flips, and with it (at 16 chunks per row) chunk bit 3
+  const char* p1 = lds + (x ^ (DH >= 128 ? 0x80u : 0u)) + (unsigned)((r0 + 8) * (DH * 2));
   const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)p0);
   const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)p1);
   const short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -671,6 +685,136 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// dQ (and delta), phases in sequence (used for DH = 128).  The same arithmetic as the kernel above
+// one 32-key half after the other: P1 = S^T and dP^T (2 KS MFMAs on two accumulators taking turns),
+// V = dS^T packed to bf16, P3 = dQ^T += K^T dS^T; two LDS buffers, one barrier per 64-key tile.
+// Its registers are budgeted for two waves per SIMD and its LDS for two workgroups per CU, so the
+// hardware interleaves the phases of two workgroups instead of the source interleaving them
+// within one wave (which at DH = 128 needs more registers than two waves per SIMD leave).
+// ---------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_phased_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
+                                                                         const float* __restrict__ lse,
+                                                                         const bf16_t* __restrict__ ctx,
+                                                                         const bf16_t* __restrict__ dctx,
+                                                                         float* __restrict__ delta,
+                                                                         bf16_t* __restrict__ dqkv) {
+  constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
+  constexpr int N1 = 2 * KS;   // score MFMAs per 32-key half: S and dP, KS each
+  constexpr int N3 = 2 * DT;   // dQ MFMAs per half: two k-steps x DT
+  constexpr int LEAD = N3;     // fragments in flight
+  constexpr int NSEG = DH / 32;
+  static_assert(2 * NSEG <= N1 && N1 % LEAD == 0, "slot plan");
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 x [K tile | V tile]
+  const int n_qt = S / 128;
+  int pair, bh;
+  pair_of_tiles(n_qt, BH, pair, bh);
+  const int b = bh / H, h = bh % H;
+  const int Hd = H * DH;
+  const size_t ld = 3 * (size_t)Hd;
+  const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
+  const float scale = rsqrtf((float)DH);
+  const float c = scale * LOG2E;
+  const unsigned sm = lds_addr(smem);
+
+  for (int pass = 0; pass < 2; pass++) {
+    const int qt = pass == 0 ? n_qt - 1 - pair : pair;
+    if (pass == 1 && qt == n_qt - 1 - pair) break;
+    const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
+    bf16x8 qf[KS], dof[KS];
+    const bf16_t* dorow = dctx + ((size_t)b * S + iq) * Hd + h * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
+      dof[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dorow + ks * 16 + g * 8));
+    }
+    float li = lse[((size_t)b * H + h) * S + iq] * LOG2E;
+    float di = 0.f;  // delta_i = sum_d dO[i, d] O[i, d], half of the row per lane
+    const bf16_t* orow = ctx + ((size_t)b * S + iq) * Hd + h * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const bf16x8 o = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(orow + ks * 16 + g * 8));
+#pragma unroll
+      for (int e = 0; e < 8; e++) di = fmaf((float)o[e], (float)dof[ks][e], di);
+    }
+    di = sum32(di);
+    if (g == 0) delta[((size_t)b * H + h) * S + iq] = di;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) { settle(qf[ks]); settle(dof[ks]); }
+    settle(li); settle(di);
+    f32x16 dq[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
+
+    const int n_kv = 2 * (qt + 1);
+    auto tile_load = [&](int j0, int buf, int i) {
+      const unsigned st = sm + buf * 2 * TB;
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
+      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
+    };
+    bf16x8 f[LEAD];  // one ring for both kinds of fragment: slot i reloads the register it has just used
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // One 64-key tile, a 32-key half at a time.  MASK: the tile may reach past the wave's first query.
+    auto tile = [&](auto mask_c, int t) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      const char* kt_ = smem + (t & 1) * 2 * TB;
+      const char* vt_ = kt_ + TB;
+      const int j0n = min(t + 1, n_kv - 1) * TR;  // past the end: the last tile again, into the buffer nobody reads
+      // P1 slot i of half jt: S (K rows x Q) or dP (V rows x dO) by bit 0, k-step i / 2
+      auto row_frag = [&](int jt, int i) { return frag_rows<DH>((i & 1) ? vt_ : kt_, jt * 32, i / 2, lane); };
+      // P3 slot i of half jt: d-tile i % DT, k-step i / DT
+      auto col_frag = [&](int jt, int i) { return frag_cols<DH>(kt_, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
+#pragma unroll
+      for (int i = 0; i < LEAD; i++) f[i] = row_frag(0, i);  // cold start: exposed once per tile
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++) {
+        f32x16 sc, dp;
+#pragma unroll
+        for (int i = 0; i < N1; i++) {
+          const int ks = i / 2;
+          if (i & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], dof[ks], i < 2 ? zero : dp, 0, 0, 0);
+          else sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], qf[ks], i < 2 ? zero : sc, 0, 0, 0);
+          if (i + LEAD < N1) f[i % LEAD] = row_frag(jt, i + LEAD);
+          else f[i % LEAD] = col_frag(jt, i + LEAD - N1);  // (N1 is a multiple of LEAD)
+          if (jt == 0 && i < 2 * NSEG) tile_load(j0n, (t + 1) & 1, i);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        bf16x8 db[2];
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[v], c, -li));
+          if (MASK && t * TR + jt * 32 + (v >> 2) * 8 + g * 4 + (v & 3) > iq) p = 0.f;
+          db[v >> 3][v & 7] = (__bf16)(p * (dp[v] - di));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N3; i++) {
+          dq[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], db[i / DT], dq[i % DT], 0, 0, 0);
+          if (jt == 0) f[i % LEAD] = row_frag(1, i);  // the second half's first rows (N3 = LEAD)
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      lds_dma_wait();
+      __syncthreads();
+    };
+
+#pragma unroll
+    for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
+    lds_dma_wait();
+    __syncthreads();
+    for (int t = 0; t < n_kv - 2; t++) tile(F_{}, t);
+    tile(T_{}, n_kv - 2);  // the last two tiles (128 keys) straddle the diagonal of this workgroup's 128 queries
+    tile(T_{}, n_kv - 1);
+
+    store_rows<DH>(dqkv + ((size_t)b * S + iq) * ld + h * DH, dq, scale, g);
+  }  // pass
+}
+
+// ---------------------------------------------------------------------------------------------
 // dK, dV.  Wave w owns keys 128 kt + 32 w .. + 31, held in registers as the B operands; 64-query
 // tiles of Q and dO (plus their lse and delta) stream through three LDS buffers, starting at the
 // diagonal.  Per 32-query half u:
@@ -895,11 +1039,18 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, cons
                  bf16_t* dqkv, float* delta, hipStream_t s) {
   constexpr size_t lds_q = 3 * (2 * (size_t)TR * DH * 2);
   constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);
-  FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
   FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
   const dim3 grid(((S / 128 + 1) / 2) * B * H);
   // dQ first: it also produces delta, which the dK/dV kernel reads
-  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
+  if constexpr (DH == 128) {
+    constexpr size_t lds_qp = 2 * (2 * (size_t)TR * DH * 2);  // two stages: two workgroups per CU
+    FAX_TRY(set_lds(attn_bwd_dq_phased_mfma_kernel<DH>, lds_qp));
+    hipLaunchKernelGGL((attn_bwd_dq_phased_mfma_kernel<DH>), grid, dim3(256), lds_qp, s, S, H, B * H, qkv, lse, ctx, dctx, delta,
+                       dqkv);
+  } else {
+    FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
+  }
   hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;
