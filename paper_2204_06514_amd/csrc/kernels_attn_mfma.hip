@@ -1002,6 +1002,144 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, in
   }  // pass
 }
 
+// ---------------------------------------------------------------------------------------------
+// dK, dV, phases in sequence (used for DH = 64, where the kernel then fits the register budget of
+// two waves per SIMD and several workgroups share a CU).  The same arithmetic as the kernel above,
+// a 32-query half at a time: P1 = S and dP (2 KS MFMAs), V = P and dS packed to bf16, P3 = dV^T and
+// dK^T (2 KS MFMAs); two LDS buffers, one barrier per 64-query tile.
+// ---------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_phased_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
+                                                                          const float* __restrict__ lse,
+                                                                          const float* __restrict__ delta,
+                                                                          const bf16_t* __restrict__ dctx,
+                                                                          bf16_t* __restrict__ dqkv) {
+  constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
+  constexpr int LD_OFF = 2 * TB, STAGE = 2 * TB + 4 * 256;  // Q tile | dO tile | lse and delta as above
+  constexpr int N = 2 * KS;                   // MFMAs per phase and half
+  constexpr int LEAD = N < 8 ? N : 8;         // fragments in flight
+  constexpr int NSEG = DH / 32;
+  static_assert(N % LEAD == 0 && 2 * NSEG + 1 <= N, "slot plan");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n_kt = S / 128;
+  int pair, bh;
+  pair_of_tiles(n_kt, BH, pair, bh);
+  const int b = bh / H, h = bh % H;
+  const int Hd = H * DH;
+  const size_t ld = 3 * (size_t)Hd;
+  const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
+  const bf16_t* dob = dctx + (size_t)b * S * Hd + h * DH;
+  const float* lrow = lse + ((size_t)b * H + h) * S;
+  const float* drow = delta + ((size_t)b * H + h) * S;
+  const int lane = threadIdx.x & 63, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const float c = rsqrtf((float)DH) * LOG2E;
+  const unsigned sm = lds_addr(smem);
+
+  for (int pass = 0; pass < 2; pass++) {
+    const int kt = pass == 0 ? pair : n_kt - 1 - pair;
+    if (pass == 1 && kt == pair) break;  // odd number of key tiles: the middle one stands alone
+    const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + Hd + ks * 16 + g * 8));
+      vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + 2 * Hd + ks * 16 + g * 8));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) { settle(kf[ks]); settle(vf[ks]); }
+    f32x16 dk[DT], dv[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
+
+    const int i_first = kt * 128;
+    const int n_q = (S - i_first) / TR;
+    auto tile_load = [&](int i0, int buf, int i) {
+      const unsigned st = sm + buf * STAGE;
+      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, wave, i);
+      else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, wave, i - NSEG);
+      else lds_dma4(((lane & 16) ? drow : lrow) + i0 + wave * 16 + (lane & 15), st + LD_OFF + wave * 256);
+    };
+    bf16x8 f[LEAD];  // one ring for both kinds of fragment: slot i reloads the register it has just used
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // One 64-query tile, a 32-query half at a time.  MASK: the tile may reach back before the wave's last key.
+    auto tile = [&](auto mask_c, int t) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      const char* st = smem + (t & 1) * STAGE;
+      const int i0n = i_first + min(t + 1, n_q - 1) * TR;  // past the end: the last tile again, into the buffer nobody reads
+      // P1 slot i of half it: S (Q rows x K) or dP (dO rows x V) by bit 0, k-step i / 2
+      auto row_frag = [&](int it, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, it * 32, i / 2, lane); };
+      // P3 slot i: dV (dO^T) or dK (Q^T) by bit 0, d-tile (i / 2) % DT, k-step i / (2 DT)
+      auto col_frag = [&](int it, int i) {
+        return frag_cols<DH>(i % 2 ? st : st + TB, ((i / 2) % DT) * 32, it * 32 + (i / (2 * DT)) * 16, lane);
+      };
+      // lse / delta of the rows 32 it + 8 q + 4 g + 0..3 that this lane meets in accumulator group q
+      auto stat4 = [&](int it, int q, int which) {
+        const int row = it * 32 + q * 8 + g * 4;
+        return *reinterpret_cast<const float4*>(st + LD_OFF + (row >> 4) * 256 + which * 64 + (row & 15) * 4);
+      };
+#pragma unroll
+      for (int i = 0; i < LEAD; i++) f[i] = row_frag(0, i);  // cold start: exposed once per tile
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int it = 0; it < 2; it++) {
+        const int i0h = i_first + t * TR + it * 32;  // first query of the half
+        f32x16 sc, dp;
+#pragma unroll
+        for (int i = 0; i < N; i++) {
+          if (i % 2 == 0) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], kf[i / 2], i < 2 ? zero : sc, 0, 0, 0);
+          else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], vf[i / 2], i < 2 ? zero : dp, 0, 0, 0);
+          if (i + LEAD < N) f[i % LEAD] = row_frag(it, i + LEAD);
+          else f[i % LEAD] = col_frag(it, i + LEAD - N);
+          if (it == 0 && i <= 2 * NSEG) tile_load(i0n, (t + 1) & 1, i);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        bf16x8 pb[2], db[2];
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const float4 l4 = stat4(it, q, 0), d4 = stat4(it, q, 1);
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            const int v = q * 4 + r;
+            float p = __builtin_amdgcn_exp2f(fmaf(sc[v], c, -LOG2E * f4_get(l4, r)));
+            if (MASK && jk > i0h + q * 8 + g * 4 + r) p = 0.f;
+            const float d = p * (dp[v] - f4_get(d4, r));
+            pb[v >> 3][v & 7] = (__bf16)p;
+            db[v >> 3][v & 7] = (__bf16)d;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N; i++) {
+          const int hh = i / (2 * DT), dt = (i / 2) % DT;
+          if (i % 2 == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], pb[hh], dv[dt], 0, 0, 0);
+          else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], db[hh], dk[dt], 0, 0, 0);
+          if (i + LEAD < N) f[i % LEAD] = col_frag(it, i + LEAD);
+          else if (it == 0) f[i % LEAD] = row_frag(1, i + LEAD - N);  // the second half's first rows
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      lds_dma_wait();
+      __syncthreads();
+    };
+
+#pragma unroll
+    for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first, 0, i);
+    lds_dma_wait();
+    __syncthreads();
+    tile(T_{}, 0);  // the first two tiles (128 queries) straddle the diagonal of this workgroup's 128 keys
+    tile(T_{}, 1);
+    for (int t = 2; t < n_q; t++) tile(F_{}, t);
+
+    const float scale = rsqrtf((float)DH);
+    bf16_t* out = dqkv + ((size_t)b * S + jk) * ld + h * DH;
+    store_rows<DH>(out + Hd, dk, scale, g);
+    store_rows<DH>(out + 2 * Hd, dv, 1.f, g);
+  }  // pass
+}
+
 bool attn_mfma_supported(int dtype, int B, int S, int H, int dh) {
   (void)B; (void)H;
   return dtype == FAX_BF16 && (dh == 64 || dh == 128) && S > 0 && S % 128 == 0;
@@ -1039,7 +1177,6 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, cons
                  bf16_t* dqkv, float* delta, hipStream_t s) {
   constexpr size_t lds_q = 3 * (2 * (size_t)TR * DH * 2);
   constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);
-  FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
   const dim3 grid(((S / 128 + 1) / 2) * B * H);
   // dQ first: it also produces delta, which the dK/dV kernel reads
   if constexpr (DH == 128) {
@@ -1051,7 +1188,15 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, cons
     FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
   }
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
+  if constexpr (DH == 64) {
+    constexpr size_t lds_kvp = 2 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // two stages
+    FAX_TRY(set_lds(attn_bwd_dkv_phased_mfma_kernel<DH>, lds_kvp));
+    hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kvp, s, S, H, B * H, qkv, lse, delta, dctx,
+                       dqkv);
+  } else {
+    FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
+  }
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;
 }
