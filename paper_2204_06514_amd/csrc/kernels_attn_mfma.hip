@@ -187,23 +187,33 @@ __device__ __forceinline__ void pair_of_tiles(int n_tiles, int BH, int& pair, in
   }
 }
 
-// The three kernels run one wave per SIMD, so nothing hides a wave's own latencies.  The work
-// on one block of keys (queries) is laid out by hand as three phases,
+// The work on one block of keys (queries) is laid out by hand as three phases,
 //   P1  MFMAs that produce scores (row fragments of the streamed tiles from LDS)
 //   V   the vector work on the scores
 //   P3  MFMAs that consume the packed probabilities (transpose-read fragments)
 // and inside P1 and P3 every MFMA is followed by the LDS read of a fragment needed LEAD MFMAs
-// later (sched_barrier pins that order), so the matrix core never waits for an LDS round trip.
+// later (sched_barrier pins that order), so the matrix core does not wait for an LDS round trip.
 // P1's last reads fetch P3's first fragments; P3's last reads fetch the next P1's first rows.
-// MFMAs that accumulate into the same registers are kept two slots apart.
+// MFMAs that accumulate into the same registers are kept at least two slots apart.
+//
+// Within one wave the three phases use different units (matrix core and LDS, vector unit, matrix
+// core and LDS) one after the other.  Two ways of filling the idle ones were built and measured:
+//   * skew: the vector work of half u rides slot by slot on the MFMAs of its neighbours within
+//     the same wave (three LDS buffers, two sets of score registers);
+//   * occupancy: keep the kernel within the register budget of two waves per SIMD and the LDS
+//     budget of two workgroups per CU and let the hardware interleave two workgroups' phases.
+// Occupancy won wherever the kernel fits (forward 208 -> 167 us and dQ 261 -> 217 us at dh = 128,
+// dK/dV 13.2 -> 11.2 ms over the 124M model's twelve layers at dh = 64; the skewed forward and dQ
+// kernels were 4-20 % slower than these and are gone).  dK/dV at dh = 128 holds 192 registers of
+// accumulators and B operands alone and stays a one-wave-per-SIMD kernel with the skew.
 
 // ---------------------------------------------------------------------------------------------
-// Forward, phases in sequence (used for DH = 128).  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
+// Forward.  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
 // K and V stream through two LDS buffers.  Per tile: P1 = S^T for both 32-key halves, V = online
 // softmax over the 64 keys, P3 = O^T += V^T P^T.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_phased_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ ctx, float* __restrict__ lse) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
   constexpr int N = 2 * KS;            // MFMAs per phase (P3: 2 halves x 2 k-steps x DT = 2 KS as well)
@@ -345,355 +355,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_phased_mfma_kernel(int S, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Forward, phases overlapped (used for DH = 64).  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
-// K and V stream through three LDS buffers.  The unit of work is a 32-key half u:
-//   P1(u): S^T(u) = K Q^T                      (row fragments of K)
-//   V(u):  online softmax over the half: running maximum, then p = 2^(c s - c m), row sums,
-//          P^T packed to bf16 straight out of the score accumulators (already in B-operand layout)
-//   P3(u): O^T += V^T P^T                      (transpose-read fragments of V)
-// The vector work is longer than both MFMA phases together, so they ride on it, skewed by one
-// half each way: iteration u is
-//   maximum phase   slot by slot: one MFMA of P3(u - 1), the read of one K fragment of half
-//                   u + 1, the maximum over 16/N scores of half u
-//   (rescale of the accumulators, only when some query's maximum moved; barrier on even u)
-//   exponent phase  slot by slot: one MFMA of P1(u + 1), the read of one V fragment of half u,
-//                   16/N exponentials of half u; on even u the loads of the tile after next
-// with two sets of score accumulators and packed probabilities taking turns.  Past the last half
-// the "next" scores are computed from the last half again and dropped.  One barrier per tile,
-// between the phases of its first half: every wave is then done with the previous tile (last read
-// by P3 of its second half, just before) and the next tile, requested a tile ago, has landed.
-// Measured against the kernel above: 22 % faster at DH = 64 (4.6 vs 5.9 ms over the twelve layers of
-// the 124M model), 17 % slower at DH = 128, where the vector unit is the bound either way (54 % busy
-// against 48 %) and this form spends 30 % more vector instructions on per-half bookkeeping.
-// ---------------------------------------------------------------------------------------------
-template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_skewed_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
-                                                            bf16_t* __restrict__ ctx, float* __restrict__ lse) {
-  constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  constexpr int STAGE = 2 * TB, NBUF = 3;  // K tile | V tile
-  constexpr int N = KS;                    // score MFMAs per half = slots of the exponent phase
-  constexpr int N3 = 2 * DT;               // output MFMAs per half = slots of the maximum phase
-  constexpr int NSEG = DH / 32;            // 1 KB load instructions per wave per tile
-  constexpr int EPS = 16 / N;              // scores per slot
-  static_assert(N == N3 && 16 % N == 0 && 2 * NSEG <= N, "slot plan");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n_qt = S / 128;
-  int pair, bh;
-  pair_of_tiles(n_qt, BH, pair, bh);
-  const int b = bh / H, h = bh % H;
-  const int Hd = H * DH;
-  const size_t ld = 3 * (size_t)Hd;
-  const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
-  const float scale = rsqrtf((float)DH);
-  const float c = scale * LOG2E;
-  const unsigned sm = lds_addr(smem);
-
-  for (int pass = 0; pass < 2; pass++) {
-    const int qt = pass == 0 ? n_qt - 1 - pair : pair;  // the long one first
-    if (pass == 1 && qt == n_qt - 1 - pair) break;      // odd number of tiles: the middle one stands alone
-    const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
-    bf16x8 qf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) settle(qf[ks]);
-    float m = -INFINITY, l = 0.f;
-    f32x16 oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) oacc[dt][v] = 0.f;
-
-    const int n_kv = 2 * (qt + 1), n_half = 2 * n_kv;
-    auto tile_load = [&](int j0, int buf, int i) {
-      const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
-      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
-    };
-    auto stage = [&](int t) { return smem + (min(t, n_kv - 1) % NBUF) * STAGE; };  // past the end: the last tile again
-    auto row_frag = [&](const char* st, int jt, int i) { return frag_rows<DH>(st, jt * 32, i, lane); };
-    // P3 slot i: d-tile i % DT (MFMAs on the same accumulator are DT slots apart), k-step i / DT
-    auto col_frag = [&](const char* st, int jt, int i) { return frag_cols<DH>(st + TB, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
-
-    bf16x8 fr[N], fc[N3];
-    f32x16 sc[2];     // [u & 1]: scores of half u
-    bf16x8 pb[2][2];  // [u & 1][k-step]: its probabilities
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // Half u (jt = u & 1 fixed at compile time).  MASK: the half may reach past the wave's first query.
-    auto step = [&](auto mask_c, auto jt_c, int u) {
-      constexpr bool MASK = decltype(mask_c)::value;
-      constexpr int JT = decltype(jt_c)::value;
-      const int t = u >> 1;
-      const char* st = stage(t);
-      const char* st1 = stage((u + 1) >> 1);
-      const int j0h = t * TR + JT * 32;  // first key of half u
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < N3; i++) {
-        oacc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i], pb[JT ^ 1][i / DT], oacc[i % DT], 0, 0, 0);
-        fr[i] = row_frag(st1, JT ^ 1, i);
-#pragma unroll
-        for (int e = 0; e < EPS; e++) {
-          const int v = i * EPS + e;
-          if (MASK && j0h + (v >> 2) * 8 + g * 4 + (v & 3) > iq) sc[JT][v] = -INFINITY;
-          mx = fmaxf(mx, sc[JT][v]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      mx = max32(mx);
-      // lazy reference point, as in the kernel above
-      const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and comes in the first half
-      if (__builtin_amdgcn_ballot_w64((mn - m) * c > MAX_LAG) != 0) {
-        const float corr = __builtin_amdgcn_exp2f((m - mn) * c);
-        l *= corr;
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) oacc[dt][v] *= corr;
-        m = mn;
-      }
-      const float mc = m * c;
-      if (JT == 0) {
-        // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
-        // half u - 1, the last reader of tile t - 1
-        lds_dma_wait();
-        __syncthreads();
-      }
-      const int j0n = min(t + 2, n_kv - 1) * TR;
-      float rs = 0.f;
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        sc[JT ^ 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], qf[i], i == 0 ? zero : sc[JT ^ 1], 0, 0, 0);
-        fc[i] = col_frag(st, JT, i);
-        if (JT == 0 && i < 2 * NSEG) tile_load(j0n, (t + 2) % NBUF, i);
-#pragma unroll
-        for (int e = 0; e < EPS; e++) {
-          const int v = i * EPS + e;
-          // scores stay unscaled; the softmax scale rides in the exponent: p = 2^(c s - c m), c = scale log2 e
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[JT][v], c, -mc));
-          rs += p;
-          pb[JT][v >> 3][v & 7] = (__bf16)p;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      l += sum32(rs);
-    };
-
-#pragma unroll
-    for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
-#pragma unroll
-    for (int i = 0; i < 2 * NSEG; i++) tile_load(TR, 1, i);
-    lds_dma_wait();
-    __syncthreads();
-    {  // scores of half 0, cold: fragment reads exposed once per pass.  The first maximum phase
-       // multiplies zero probabilities with (finite) values of half 0.
-      const char* st = stage(0);
-#pragma unroll
-      for (int i = 0; i < N; i++) fr[i] = row_frag(st, 0, i);
-#pragma unroll
-      for (int i = 0; i < N3; i++) fc[i] = col_frag(st, 0, i);
-#pragma unroll
-      for (int hh = 0; hh < 2; hh++)
-#pragma unroll
-        for (int e = 0; e < 8; e++) pb[1][hh][e] = (__bf16)0.f;
-#pragma unroll
-      for (int i = 0; i < N; i++) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], qf[i], i == 0 ? zero : sc[0], 0, 0, 0);
-    }
-    for (int u = 0; u < n_half - 4; u += 2) {
-      step(F_{}, I<0>{}, u);
-      step(F_{}, I<1>{}, u + 1);
-    }
-    // the last two tiles (four halves) straddle the diagonal of this workgroup's 128 queries
-    step(T_{}, I<0>{}, n_half - 4);
-    step(T_{}, I<1>{}, n_half - 3);
-    step(T_{}, I<0>{}, n_half - 2);
-    step(T_{}, I<1>{}, n_half - 1);
-#pragma unroll
-    for (int i = 0; i < N3; i++)  // P3 of the last half
-      oacc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i], pb[1][i / DT], oacc[i % DT], 0, 0, 0);
-    lds_dma_wait();   // the re-requested last tile
-    __syncthreads();  // LDS is reused by the next pass
-
-    store_rows<DH>(ctx + ((size_t)b * S + iq) * Hd + h * DH, oacc, 1.f / l, g);
-    if (g == 0) lse[((size_t)b * H + h) * S + iq] = m * scale + logf(l);
-  }  // pass
-}
-
-// ---------------------------------------------------------------------------------------------
 // dQ (and delta).  Wave w owns queries 128 qt + 32 w .. + 31 (Q and dO rows in registers as B
-// operands); 64-key tiles of K and V stream through three LDS buffers.  Per 32-key half u:
-//   S^T(u) = K Q^T and dP^T(u) = V dO^T, alternating (row fragments of K and V)
-//   V(u): dS^T = P^T (dP^T - delta), P^T = 2^(c S^T - lse log2 e), packed to bf16
-//   P3(u): dQ^T += K^T dS^T (transpose-read fragments of K)
-// laid out like the dK/dV kernel below: C(u) = score MFMAs of half u + 1 with V(u) riding on
-// them, then P3(u); one barrier per tile, before P3 of its first half.
+// operands); 64-key tiles of K and V stream through two LDS buffers.  One 32-key half after the
+// other:
+//   P1: S^T = K Q^T and dP^T = V dO^T, alternating (row fragments of K and V, 2 KS MFMAs)
+//   V:  dS^T = P^T (dP^T - delta), P^T = 2^(c S^T - lse log2 e), packed to bf16
+//   P3: dQ^T += K^T dS^T (transpose-read fragments of K)
+// One barrier per 64-key tile.  Registers budgeted for two waves per SIMD, LDS for two workgroups
+// per CU (see above).
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
-                                                               const float* __restrict__ lse,
-                                                               const bf16_t* __restrict__ ctx,
-                                                               const bf16_t* __restrict__ dctx,
-                                                               float* __restrict__ delta,
-                                                               bf16_t* __restrict__ dqkv) {
-  constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  constexpr int STAGE = 2 * TB, NBUF = 3;  // K tile | V tile
-  constexpr int N = 2 * KS;            // score MFMAs per half
-  constexpr int N3 = 2 * DT;           // dQ MFMAs per half (= KS)
-  constexpr int LEAD = N < 8 ? N : 8;  // fragments in flight
-  constexpr int NSEG = DH / 32;
-  constexpr int EPS = 16 / N;          // score elements per slot of C
-  static_assert(N3 <= LEAD && 2 * NSEG <= N3 && 16 % N == 0, "slot plan");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n_qt = S / 128;
-  int pair, bh;
-  pair_of_tiles(n_qt, BH, pair, bh);
-  const int b = bh / H, h = bh % H;
-  const int Hd = H * DH;
-  const size_t ld = 3 * (size_t)Hd;
-  const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 5;
-  const float scale = rsqrtf((float)DH);
-  const float c = scale * LOG2E;
-  const unsigned sm = lds_addr(smem);
-
-  for (int pass = 0; pass < 2; pass++) {
-    const int qt = pass == 0 ? n_qt - 1 - pair : pair;
-    if (pass == 1 && qt == n_qt - 1 - pair) break;
-    const int q0w = qt * 128 + wave * 32, iq = q0w + (lane & 31);
-    bf16x8 qf[KS], dof[KS];
-    const bf16_t* dorow = dctx + ((size_t)b * S + iq) * Hd + h * DH;
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)iq * ld + ks * 16 + g * 8));
-      dof[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dorow + ks * 16 + g * 8));
-    }
-    float li = lse[((size_t)b * H + h) * S + iq] * LOG2E;
-    // delta_i = sum_d dO[i, d] O[i, d]: this lane holds half of row i of dO (the d's of its k-slots);
-    // its partner lane (lane ^ 32) holds the other half.  Also stored for the dK/dV kernel.
-    float di = 0.f;
-    const bf16_t* orow = ctx + ((size_t)b * S + iq) * Hd + h * DH;
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      const bf16x8 o = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(orow + ks * 16 + g * 8));
-#pragma unroll
-      for (int e = 0; e < 8; e++) di = fmaf((float)o[e], (float)dof[ks][e], di);
-    }
-    di = sum32(di);
-    if (g == 0) delta[((size_t)b * H + h) * S + iq] = di;
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) { settle(qf[ks]); settle(dof[ks]); }
-    settle(li); settle(di);
-    f32x16 dq[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
-
-    const int n_kv = 2 * (qt + 1), n_half = 2 * n_kv;
-    auto tile_load = [&](int j0, int buf, int i) {
-      const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)j0 * ld + Hd, ld, wave, i);
-      else tile_dma_seg<DH>(st + TB, base + (size_t)j0 * ld + 2 * Hd, ld, wave, i - NSEG);
-    };
-    auto stage = [&](int t) { return smem + (min(t, n_kv - 1) % NBUF) * STAGE; };  // past the end: the last tile again
-    auto row_frag = [&](const char* st, int jt, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, jt * 32, i / 2, lane); };
-    auto col_frag = [&](const char* st, int jt, int i) { return frag_cols<DH>(st, (i % DT) * 32, jt * 32 + (i / DT) * 16, lane); };
-
-    bf16x8 fr[LEAD], fc[LEAD];
-    f32x16 sc[2], dp[2];  // [u & 1]: scores of half u
-    bf16x8 db[2];
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    auto score_mfma = [&](int par, int i) {
-      if (i % 2 == 0) sc[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], i < 2 ? zero : sc[par], 0, 0, 0);
-      else dp[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], dof[i / 2], i < 2 ? zero : dp[par], 0, 0, 0);
-    };
-    // Half u (jt = u & 1 fixed at compile time): C(u), [barrier], P3(u).
-    auto step = [&](auto mask_c, auto jt_c, int u) {
-      constexpr bool MASK = decltype(mask_c)::value;
-      constexpr int JT = decltype(jt_c)::value;
-      const int t = u >> 1;
-      const char* st = stage(t);
-      const char* st1 = stage((u + 1) >> 1);
-      const char* st2 = stage(t + 1);
-      const int j0h = t * TR + JT * 32;  // first key of half u
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        score_mfma(JT ^ 1, i);
-        if (i + LEAD < N) fr[i % LEAD] = row_frag(st1, JT ^ 1, i + LEAD);
-        else if (i + LEAD - N < N3) fc[i + LEAD - N] = col_frag(st, JT, i + LEAD - N);
-#pragma unroll
-        for (int e = 0; e < EPS; e++) {
-          const int v = i * EPS + e;
-          float p = __builtin_amdgcn_exp2f(fmaf(sc[JT][v], c, -li));
-          if (MASK && j0h + (v >> 2) * 8 + g * 4 + (v & 3) > iq) p = 0.f;
-          db[v >> 3][v & 7] = (__bf16)(p * (dp[JT][v] - di));
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (JT == 0) {
-        // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
-        // half u - 1, the last reader of tile t - 1
-        lds_dma_wait();
-        __syncthreads();
-      }
-      const int j0n = min(t + 2, n_kv - 1) * TR;
-#pragma unroll
-      for (int i = 0; i < N3; i++) {
-        dq[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i], db[i / DT], dq[i % DT], 0, 0, 0);
-        if (i < LEAD) fr[i] = row_frag(st2, JT, i);
-        if (JT == 0 && i < 2 * NSEG) tile_load(j0n, (t + 2) % NBUF, i);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-#pragma unroll
-      for (int i = N3; i < LEAD; i++) fr[i] = row_frag(st2, JT, i);
-    };
-
-#pragma unroll
-    for (int i = 0; i < 2 * NSEG; i++) tile_load(0, 0, i);
-#pragma unroll
-    for (int i = 0; i < 2 * NSEG; i++) tile_load(TR, 1, i);
-    lds_dma_wait();
-    __syncthreads();
-    {  // scores of half 0, cold: fragment reads exposed once per pass
-      const char* st = stage(0);
-#pragma unroll
-      for (int i = 0; i < LEAD; i++) fr[i] = row_frag(st, 0, i);
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        score_mfma(0, i);
-        if (i + LEAD < N) fr[i % LEAD] = row_frag(st, 0, i + LEAD);
-        else fr[i + LEAD - N] = row_frag(st, 1, i + LEAD - N);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    for (int u = 0; u < n_half - 4; u += 2) {
-      step(F_{}, I<0>{}, u);
-      step(F_{}, I<1>{}, u + 1);
-    }
-    // the last two tiles (four halves) straddle the diagonal of this workgroup's 128 queries
-    step(T_{}, I<0>{}, n_half - 4);
-    step(T_{}, I<1>{}, n_half - 3);
-    step(T_{}, I<0>{}, n_half - 2);
-    step(T_{}, I<1>{}, n_half - 1);
-    lds_dma_wait();   // the re-requested last tile
-    __syncthreads();  // LDS is reused by the next pass
-
-    store_rows<DH>(dqkv + ((size_t)b * S + iq) * ld + h * DH, dq, scale, g);
-  }  // pass
-}
-
-// ---------------------------------------------------------------------------------------------
-// dQ (and delta), phases in sequence (used for DH = 128).  The same arithmetic as the kernel above
-// one 32-key half after the other: P1 = S^T and dP^T (2 KS MFMAs on two accumulators taking turns),
-// V = dS^T packed to bf16, P3 = dQ^T += K^T dS^T; two LDS buffers, one barrier per 64-key tile.
-// Its registers are budgeted for two waves per SIMD and its LDS for two workgroups per CU, so the
-// hardware interleaves the phases of two workgroups instead of the source interleaving them
-// within one wave (which at DH = 128 needs more registers than two waves per SIMD leave).
-// ---------------------------------------------------------------------------------------------
-template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_phased_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                                          const float* __restrict__ lse,
                                                                          const bf16_t* __restrict__ ctx,
                                                                          const bf16_t* __restrict__ dctx,
@@ -815,7 +487,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_phased_mfma_kernel(int S, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK, dV.  Wave w owns keys 128 kt + 32 w .. + 31, held in registers as the B operands; 64-query
+// dK, dV (used for DH = 128).  Wave w owns keys 128 kt + 32 w .. + 31, held in registers as the B operands; 64-query
 // tiles of Q and dO (plus their lse and delta) stream through three LDS buffers, starting at the
 // diagonal.  Per 32-query half u:
 //   S(u) = Q K^T and dP(u) = dO V^T, alternating (row fragments of Q and dO)
@@ -1003,7 +675,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK, dV, phases in sequence (used for DH = 64, where the kernel then fits the register budget of
+// dK, dV without the skew (used for DH = 64, where the kernel then fits the register budget of
 // two waves per SIMD and several workgroups share a CU).  The same arithmetic as the kernel above,
 // a 32-query half at a time: P1 = S and dP (2 KS MFMAs), V = P and dS packed to bf16, P3 = dV^T and
 // dK^T (2 KS MFMAs); two LDS buffers, one barrier per 64-query tile.
@@ -1153,16 +825,10 @@ static int set_lds(K kern, size_t bytes) {
 
 template <int DH>
 static int fwd_t(int B, int S, int H, const bf16_t* qkv, bf16_t* ctx, float* lse, hipStream_t s) {
-  const dim3 grid(((S / 128 + 1) / 2) * B * H);
-  if constexpr (DH == 64) {
-    constexpr size_t lds = 3 * (2 * (size_t)TR * DH * 2);  // three stages of K tile | V tile
-    FAX_TRY(set_lds(attn_fwd_skewed_mfma_kernel<DH>, lds));
-    hipLaunchKernelGGL((attn_fwd_skewed_mfma_kernel<DH>), grid, dim3(256), lds, s, S, H, B * H, qkv, ctx, lse);
-  } else {
-    constexpr size_t lds = 2 * (2 * (size_t)TR * DH * 2);  // two stages
-    FAX_TRY(set_lds(attn_fwd_phased_mfma_kernel<DH>, lds));
-    hipLaunchKernelGGL((attn_fwd_phased_mfma_kernel<DH>), grid, dim3(256), lds, s, S, H, B * H, qkv, ctx, lse);
-  }
+  constexpr size_t lds = 2 * (2 * (size_t)TR * DH * 2);  // two stages of K tile | V tile
+  FAX_TRY(set_lds(attn_fwd_mfma_kernel<DH>, lds));
+  hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH>), dim3(((S / 128 + 1) / 2) * B * H), dim3(256), lds, s, S, H, B * H, qkv, ctx,
+                     lse);
   FAX_LAUNCH_CHECK("attn_fwd_mfma");
   return FAX_OK;
 }
@@ -1175,25 +841,18 @@ int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float
 template <int DH>
 static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx,
                  bf16_t* dqkv, float* delta, hipStream_t s) {
-  constexpr size_t lds_q = 3 * (2 * (size_t)TR * DH * 2);
-  constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);
+  constexpr size_t lds_q = 2 * (2 * (size_t)TR * DH * 2);  // two stages of K tile | V tile
   const dim3 grid(((S / 128 + 1) / 2) * B * H);
   // dQ first: it also produces delta, which the dK/dV kernel reads
-  if constexpr (DH == 128) {
-    constexpr size_t lds_qp = 2 * (2 * (size_t)TR * DH * 2);  // two stages: two workgroups per CU
-    FAX_TRY(set_lds(attn_bwd_dq_phased_mfma_kernel<DH>, lds_qp));
-    hipLaunchKernelGGL((attn_bwd_dq_phased_mfma_kernel<DH>), grid, dim3(256), lds_qp, s, S, H, B * H, qkv, lse, ctx, dctx, delta,
-                       dqkv);
-  } else {
-    FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
-  }
+  FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
+  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
   if constexpr (DH == 64) {
-    constexpr size_t lds_kvp = 2 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // two stages
-    FAX_TRY(set_lds(attn_bwd_dkv_phased_mfma_kernel<DH>, lds_kvp));
-    hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kvp, s, S, H, B * H, qkv, lse, delta, dctx,
+    constexpr size_t lds_kv = 2 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // two stages of Q tile | dO tile | lse, delta
+    FAX_TRY(set_lds(attn_bwd_dkv_phased_mfma_kernel<DH>, lds_kv));
+    hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx,
                        dqkv);
   } else {
+    constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // three stages
     FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
   }
