@@ -67,9 +67,9 @@ bool gemm_mfma_supported(const GemmArgs& g);
 // A weight-gradient product of a narrow model has few output tiles and a very long contraction
 // (K = all tokens): it is then cut into K ranges, each a full set of tiles writing its own fp32
 // partial product (and partial column sums), summed afterwards in a fixed order.  The plan (tile
-// edge, number of ranges; 1 = no split) comes from a small cost model of the kernel.
+// class, number of ranges; 1 = no split) comes from a small cost model of the kernel.
 struct GemmSplitPlan {
-  int tile;    // 256 or 128; 0: shape not supported
+  int tile_m, tile_n;  // 256 x 256, 256 x 128 or 128 x 128; 0: no tile class divides the shape
   int splits;
 };
 GemmSplitPlan gemm_split_plan(int M, int N, int K);

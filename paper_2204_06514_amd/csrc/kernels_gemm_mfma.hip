@@ -523,44 +523,79 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // computed on hosts without a GPU too).
 static constexpr int kCUs = 256;
 
-static int pick_tile_mn(int M, int N) {
-  if (M % 256 == 0 && N % 256 == 0 && (size_t)(M / 256) * (N / 256) >= 128) return 256;
-  if (M % 128 == 0 && N % 128 == 0) return 128;
-  return 0;
+// Tile classes of the kernel, largest first, and what a workgroup pays per 64-wide K slab and per
+// tile (microseconds, fitted to timings of this kernel).  The slab time is given for a full chip
+// (`full_us`) and falls with the share of busy CUs towards `floor_us`: with fewer CUs busy the
+// clock is higher (256^2: 1.55 us with all CUs busy, 1.15 with half of them) and each gets more of
+// the L2s' bandwidth, which is what bounds the 256 x 128 class on a full chip (13.7 TB/s into LDS
+// over all CUs: 0.89 us a slab on 256 CUs, 0.64 on 160).  The smaller the tile, the more LDS
+// fragment traffic per flop (4 + 4 fragments per 16 MFMAs at 256^2, 4 + 2 per 8 at 256 x 128,
+// 2 + 2 per 4 at 128^2).
+struct TileClass {
+  int m, n;
+  double full_us, idle_share, floor_us;  // slab time = max(floor, full * (idle_share + (1 - idle_share) * busy share))
+  double epi_bf16_us, epi_f32_us;
+};
+static constexpr TileClass kTiles[] = {{256, 256, 1.55, 0.48, 1.10, 7.0, 8.0},
+                                       {256, 128, 0.89, 0.25, 0.64, 4.0, 4.5},
+                                       {128, 128, 0.66, 1.00, 0.66, 3.0, 3.0}};
+
+// Predicted duration of one launch: workgroups run in rounds of one per CU, the last one possibly
+// partly filled (a 128^2 launch of at most two per CU runs them side by side, at shared LDS
+// bandwidth); folding s partial products costs a launch plus their bytes, written once and read once.
+static double tile_time_us(const TileClass& tc, int M, int N, int K, bool f32_out, int s) {
+  const int slabs = (K / GK + s - 1) / s;
+  const long long items = (long long)(M / tc.m) * (N / tc.n) * s;
+  const double epi = f32_out ? tc.epi_f32_us : tc.epi_bf16_us;
+  auto round_us = [&](double busy_share) {
+    return slabs * std::max(tc.floor_us, tc.full_us * (tc.idle_share + (1.0 - tc.idle_share) * busy_share)) + epi;
+  };
+  double t;
+  if (tc.m == 128 && items > kCUs && items <= 2 * kCUs && !f32_out) {
+    t = 1.6 * round_us(1.0);
+  } else {
+    // (weight-gradient products, both operands through the LDS transpose read, gain nothing from a
+    // partly filled round: every round at the full-chip price reproduces their measured plans)
+    const long long full = items / kCUs, rest = items % kCUs;
+    t = full * round_us(1.0) + (rest ? round_us(f32_out ? 1.0 : (double)rest / kCUs) : 0.0);
+  }
+  if (s > 1) t += 10.0 + (2.0 * s + 1.0) * M * N * 4.0 / 3.0e6;
+  return t;
 }
 
-// Cost model behind the plan, in microseconds, from timings of this kernel on fp32-output
-// products: a K slab costs a workgroup 1.55 us at 256^2 and 0.66 us at 128^2 (a quarter of the
-// work at not even half the time: twice the LDS traffic per flop), the fp32 epilogue 8 and
-// 3 us; workgroups run in rounds of one per CU; folding s partial products costs a launch plus
-// their bytes, written once and read once.
-GemmSplitPlan gemm_split_plan(int M, int N, int K) {
-  GemmSplitPlan best{pick_tile_mn(M, N), 1};
-  if (best.tile == 0 || K % GK) return best;
+// Tile class (and, when `may_split`, number of K ranges) with the smallest predicted time; a
+// smaller tile or a split has to be 3 % better than what is already chosen.  tile_m = 0: no class
+// divides the shape.  The 256 x 128 class is used for bf16 outputs only: on weight-gradient
+// products (both operands through the LDS transpose read, with or without K ranges) it measured
+// 10-50 % above this model.
+static GemmSplitPlan plan_tiles(int M, int N, int K, bool f32_out, bool may_split) {
+  GemmSplitPlan best{0, 0, 1};
+  if (M <= 0 || N <= 0 || K <= 0 || K % GK) return best;
   const int nkt = K / GK;
   double best_t = 1e30;
-  for (int bt = 256; bt >= 128; bt /= 2) {
-    if (M % bt || N % bt) continue;
-    const double t_slab = bt == 256 ? 1.55 : 0.66, t_epi = bt == 256 ? 8.0 : 3.0;
-    const long long tiles = (long long)(M / bt) * (N / bt);
-    for (int s = 1; s <= 32 && nkt / s >= 8; s++) {
-      const long long rounds = (tiles * s + kCUs - 1) / kCUs;
-      double t = rounds * ((nkt + s - 1) / s * t_slab + t_epi);
-      if (s > 1) t += 10.0 + (2.0 * s + 1.0) * M * N * 4.0 / 3.0e6;
-      if (t < best_t * 0.97) {  // a split has to pay for itself
+  for (const TileClass& tc : kTiles) {
+    if (M % tc.m || N % tc.n) continue;
+    if (f32_out && tc.m != tc.n) continue;
+    for (int s = 1; s <= (may_split ? 32 : 1) && (s == 1 || nkt / s >= 8); s++) {
+      const double t = tile_time_us(tc, M, N, K, f32_out, s);
+      if (t < best_t * 0.97) {
         best_t = t;
-        best = GemmSplitPlan{bt, s};
+        best = GemmSplitPlan{tc.m, tc.n, s};
       }
     }
   }
   return best;
 }
 
-// One dimension an odd multiple of 128 and the rest big enough for 256^2 tiles: the product is
-// computed as two, the bulk on 256^2 tiles and the last 128 rows (1) or columns (2) on 128^2 tiles.
+GemmSplitPlan gemm_split_plan(int M, int N, int K) { return plan_tiles(M, N, K, true, true); }
+
+// One dimension an odd multiple of 128 and the rest big enough to fill the chip with 256^2 tiles:
+// the product is computed as two, the bulk on 256^2 tiles and the last 128 rows (1) or columns (2)
+// on smaller ones.
 static int tail_dim(int M, int N) {
-  if (M % 256 == 128 && N % 256 == 0 && pick_tile_mn(M - 128, N) == 256) return 1;
-  if (N % 256 == 128 && M % 256 == 0 && pick_tile_mn(M, N - 128) == 256) return 2;
+  auto fills = [](int m, int n) { return m > 0 && n > 0 && m % 256 == 0 && n % 256 == 0 && (long long)(m / 256) * (n / 256) >= 2 * kCUs; };
+  if (M % 256 == 128 && fills(M - 128, N)) return 1;
+  if (N % 256 == 128 && fills(M, N - 128)) return 2;
   return 0;
 }
 
@@ -576,16 +611,11 @@ size_t gemm_split_ws_bytes(int M, int N, int K) {
 }
 
 static double time_estimate_1(int M, int N, int K, bool f32_out) {
-  const GemmSplitPlan plan = f32_out ? gemm_split_plan(M, N, K) : GemmSplitPlan{pick_tile_mn(M, N), 1};
-  if (plan.tile == 0 || K % GK) return 2.0 * M * N * K / 15.0e6;  // the scalar kernel: about 15 TFLOP/s
-  const int s = plan.splits, nkt = K / GK;
-  const double t_slab = plan.tile == 256 ? 1.55 : 0.66;
-  const double t_epi = plan.tile == 256 ? (f32_out ? 8.0 : 7.0) : 3.0;
-  const long long tiles = (long long)(M / plan.tile) * (N / plan.tile);
-  const long long rounds = (tiles * s + kCUs - 1) / kCUs;
-  double t = 3.0 + rounds * ((nkt + s - 1) / s * t_slab + t_epi);
-  if (s > 1) t += 10.0 + (2.0 * s + 1.0) * M * N * 4.0 / 3.0e6;
-  return t;
+  const GemmSplitPlan plan = plan_tiles(M, N, K, f32_out, f32_out);
+  if (plan.tile_m == 0) return 2.0 * M * N * K / 15.0e6;  // the scalar kernel: about 15 TFLOP/s
+  for (const TileClass& tc : kTiles)
+    if (tc.m == plan.tile_m && tc.n == plan.tile_n) return 3.0 + tile_time_us(tc, M, N, K, f32_out, plan.splits);
+  return 0.0;
 }
 
 double gemm_time_estimate_us(int M, int N, int K, bool f32_out) {
@@ -596,7 +626,6 @@ double gemm_time_estimate_us(int M, int N, int K, bool f32_out) {
   return time_estimate_1(M, N, K, f32_out);
 }
 
-static int pick_tile(const GemmArgs& g) { return pick_tile_mn(g.M, g.N); }
 
 bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.dtype != FAX_BF16) return false;
@@ -617,19 +646,19 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     if (!vec_ok(g.C, g.ldc) || !vec_ok(g.C2, g.ldc2) || !vec_ok(g.R, g.ldr) || !vec_ok(g.U, g.ldu) || !vec_ok(g.bias, 4))
       return false;
   }
-  return pick_tile(g) != 0;
+  return g.M % 128 == 0 && g.N % 128 == 0;  // the smallest tile class
 }
 
-template <int BT, bool A_KC, bool B_KC, int EM>
+template <int BM, int BN, bool A_KC, bool B_KC, int EM>
 static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
-  constexpr size_t lds = 3 * (size_t)TileLds<BT, A_KC>::BYTES + 2 * (size_t)TileLds<BT, B_KC>::BYTES;  // 160 KB at 256^2; also covers the epilogue's 4 x 64 x (BT/2) floats
-  auto kern = gemm_mfma_kernel<BT, BT, A_KC, B_KC, EM>;
+  constexpr size_t lds = 3 * (size_t)TileLds<BM, A_KC>::BYTES + 2 * (size_t)TileLds<BN, B_KC>::BYTES;  // 160 KB at 256^2; also covers the epilogue's staging
+  auto kern = gemm_mfma_kernel<BM, BN, A_KC, B_KC, EM>;
   static bool configured = false;  // benign race: the attribute is idempotent
   if (!configured) {
     FAX_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     configured = true;
   }
-  const int tiles_m = g.M / BT, tiles_n = g.N / BT;
+  const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   static int n_cu = 0;  // benign race: same value from every thread
   if (n_cu == 0) {
     int dev = 0, v = 0;
@@ -642,7 +671,7 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   // so two fit on a CU; they share its LDS bandwidth, which bounds that kernel, and gain little
   // (measured: +-0.4 % with many tiles) except when that saves a second round for a few left-over
   // tiles (320 tiles: -4 % on the whole step).
-  const int slots = (BT == 128 && items <= 2 * n_cu) ? 2 * n_cu : n_cu;
+  const int slots = (BM == 128 && items <= 2 * n_cu) ? 2 * n_cu : n_cu;
   const int grid = items < slots ? items : slots;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.M, g.N, g.K, (const bf16_t*)g.A, g.lda,
                      (const bf16_t*)g.B, g.ldb, e, tiles_m, tiles_n);
@@ -650,42 +679,42 @@ static int launch_mfma(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   return FAX_OK;
 }
 
-template <int BT>
+template <int BM, int BN>
 static int dispatch(const GemmArgs& g, const EpiArgs& e, hipStream_t s) {
   const bool a_kc = !g.ta, b_kc = g.tb;
   const bool erf = g.gelu_form == FAX_GELU_ERF;
   if (g.epi == EPI_GELU)
-    return erf ? launch_mfma<BT, true, false, EK_GELU_ERF>(g, e, s) : launch_mfma<BT, true, false, EK_GELU_TANH>(g, e, s);
+    return erf ? launch_mfma<BM, BN, true, false, EK_GELU_ERF>(g, e, s) : launch_mfma<BM, BN, true, false, EK_GELU_TANH>(g, e, s);
   if (g.epi == EPI_DGELU)
-    return launch_mfma<BT, true, true, EK_DGELU>(g, e, s);
+    return launch_mfma<BM, BN, true, true, EK_DGELU>(g, e, s);
   if (g.c_f32 && g.colsum)
-    return g.accumulate ? launch_mfma<BT, false, false, EK_F32 | EM_RES | EM_COLSUM>(g, e, s)
-                        : launch_mfma<BT, false, false, EK_F32 | EM_COLSUM>(g, e, s);
+    return g.accumulate ? launch_mfma<BM, BN, false, false, EK_F32 | EM_RES | EM_COLSUM>(g, e, s)
+                        : launch_mfma<BM, BN, false, false, EK_F32 | EM_COLSUM>(g, e, s);
   if (g.c_f32) {
     if (g.accumulate) {
-      if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_F32 | EM_RES>(g, e, s);
-      if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_F32 | EM_RES>(g, e, s);
-      if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_F32 | EM_RES>(g, e, s);
-      return launch_mfma<BT, false, false, EK_F32 | EM_RES>(g, e, s);
+      if (a_kc && b_kc) return launch_mfma<BM, BN, true, true, EK_F32 | EM_RES>(g, e, s);
+      if (a_kc && !b_kc) return launch_mfma<BM, BN, true, false, EK_F32 | EM_RES>(g, e, s);
+      if (!a_kc && b_kc) return launch_mfma<BM, BN, false, true, EK_F32 | EM_RES>(g, e, s);
+      return launch_mfma<BM, BN, false, false, EK_F32 | EM_RES>(g, e, s);
     }
-    if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_F32>(g, e, s);
-    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_F32>(g, e, s);
-    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_F32>(g, e, s);
-    return launch_mfma<BT, false, false, EK_F32>(g, e, s);
+    if (a_kc && b_kc) return launch_mfma<BM, BN, true, true, EK_F32>(g, e, s);
+    if (a_kc && !b_kc) return launch_mfma<BM, BN, true, false, EK_F32>(g, e, s);
+    if (!a_kc && b_kc) return launch_mfma<BM, BN, false, true, EK_F32>(g, e, s);
+    return launch_mfma<BM, BN, false, false, EK_F32>(g, e, s);
   }
   if (g.C2)  // forward orientation (checked by gemm_mfma_supported)
-    return g.R ? launch_mfma<BT, true, false, EK_STORE | EM_RES | EM_C2>(g, e, s)
-               : launch_mfma<BT, true, false, EK_STORE | EM_C2>(g, e, s);
+    return g.R ? launch_mfma<BM, BN, true, false, EK_STORE | EM_RES | EM_C2>(g, e, s)
+               : launch_mfma<BM, BN, true, false, EK_STORE | EM_C2>(g, e, s);
   if (g.R) {
-    if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_STORE | EM_RES>(g, e, s);
-    if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_STORE | EM_RES>(g, e, s);
-    if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_STORE | EM_RES>(g, e, s);
-    return launch_mfma<BT, false, false, EK_STORE | EM_RES>(g, e, s);
+    if (a_kc && b_kc) return launch_mfma<BM, BN, true, true, EK_STORE | EM_RES>(g, e, s);
+    if (a_kc && !b_kc) return launch_mfma<BM, BN, true, false, EK_STORE | EM_RES>(g, e, s);
+    if (!a_kc && b_kc) return launch_mfma<BM, BN, false, true, EK_STORE | EM_RES>(g, e, s);
+    return launch_mfma<BM, BN, false, false, EK_STORE | EM_RES>(g, e, s);
   }
-  if (a_kc && b_kc) return launch_mfma<BT, true, true, EK_STORE>(g, e, s);
-  if (a_kc && !b_kc) return launch_mfma<BT, true, false, EK_STORE>(g, e, s);
-  if (!a_kc && b_kc) return launch_mfma<BT, false, true, EK_STORE>(g, e, s);
-  return launch_mfma<BT, false, false, EK_STORE>(g, e, s);
+  if (a_kc && b_kc) return launch_mfma<BM, BN, true, true, EK_STORE>(g, e, s);
+  if (a_kc && !b_kc) return launch_mfma<BM, BN, true, false, EK_STORE>(g, e, s);
+  if (!a_kc && b_kc) return launch_mfma<BM, BN, false, true, EK_STORE>(g, e, s);
+  return launch_mfma<BM, BN, false, false, EK_STORE>(g, e, s);
 }
 
 static const void* offset(const void* p, size_t elements, size_t elem_bytes) {
@@ -725,8 +754,11 @@ int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   // Split the contraction?  Only the fp32-output form, with scratch from the caller and C stored
   // densely; the partial products (and partial column sums) are then folded in a fixed order.
-  GemmSplitPlan plan{pick_tile(g), 1};
-  if (g.c_f32 && g.split_ws && g.ldc == g.N) plan = gemm_split_plan(g.M, g.N, g.K);
+  const GemmSplitPlan plan = plan_tiles(g.M, g.N, g.K, g.c_f32, g.c_f32 && g.split_ws && g.ldc == g.N);
+  if (plan.tile_m == 0) {
+    set_error("gemm_mfma: %d x %d x %d fits no tile class", g.M, g.N, g.K);
+    return FAX_ERR_UNSUPPORTED;
+  }
   const int splits = plan.splits;
   const size_t mn = (size_t)g.M * g.N;
   float* const part_c = (float*)g.split_ws;
@@ -738,7 +770,9 @@ int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
   }
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
             g.accumulate ? 1 : 0, g.colsum, splits, mn, (size_t)g.N};
-  FAX_TRY(plan.tile == 256 ? dispatch<256>(g, e, s) : dispatch<128>(g, e, s));
+  if (plan.tile_n == 256) FAX_TRY((dispatch<256, 256>(g, e, s)));
+  else if (plan.tile_m == 256) FAX_TRY((dispatch<256, 128>(g, e, s)));
+  else FAX_TRY((dispatch<128, 128>(g, e, s)));
   if (splits > 1) {
     FAX_TRY(fold_partials(splits, mn, part_c, (float*)g0.C, g0.accumulate, s));
     if (g0.colsum) FAX_TRY(fold_partials(splits, (size_t)g.N, part_cs, g0.colsum, g0.accumulate, s));

@@ -45,6 +45,11 @@ GEMM_CASES = [
     ("bf16", fax.PATH_MFMA, 0, 1, 2048, 4224, 64),
     ("bf16", fax.PATH_MFMA, 1, 0, 4224, 2048, 192),
     ("bf16", fax.PATH_MFMA, 1, 1, 2048, 4224, 128),
+    # too few 256^2 tiles for the chip, more than one round of 128^2 tiles: the 256 x 128 tile class
+    ("bf16", fax.PATH_MFMA, 0, 0, 2048, 2560, 320),
+    ("bf16", fax.PATH_MFMA, 0, 1, 2048, 2560, 192),
+    ("bf16", fax.PATH_MFMA, 1, 0, 2048, 2560, 128),
+    ("bf16", fax.PATH_MFMA, 1, 1, 2048, 2560, 256),
 ]
 
 

@@ -11,7 +11,7 @@ registers they occupy.  Two things therefore have to hold in the emitted gfx950 
     straight-line order (which is how the main loop is laid out) with that counter, a workgroup
     barrier is never reached with more of them in flight than one operand slab's worth per wave
     (the A slab just requested, which no wave reads before a later barrier: 8 instructions at
-    256^2 tiles, 4 at 128^2), and the program never ends with any in flight.
+    256-row tiles, 4 at 128-row tiles), and the program never ends with any in flight.
 
 Compiler-issued loads are the compiler's own business and are not modelled here."""
 import os
@@ -34,7 +34,7 @@ def scan(asm_text):
     for k in kernels[1:]:
         name = k.split(":")[0]
         problems, in_asm, in_flight = [], False, 0
-        allowed = 8 if "ILi256ELi256E" in name else 4
+        allowed = 8 if "ILi256ELi" in name else 4   # the A slab: 8 load instructions per wave at 256 rows, 4 at 128
         for ln in k.split("s_endpgm")[0].split("\n") + ["s_endpgm"]:
             if "#ASMSTART" in ln:
                 in_asm = True
@@ -90,5 +90,5 @@ def test_direct_to_lds_loads_are_waited_for(tmp_path):
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
     n, bad = scan(out.read_text())
-    assert n >= 20, n
+    assert n >= 60, n
     assert not bad, {k: v[:3] for k, v in bad.items()}
