@@ -152,6 +152,29 @@ def test_attention_mfma_path(B, S, H, dh, scale):
     assert e_ctx <= 8e-3 and e_lse <= 2e-4 and max(errs) <= 1e-2, (e_ctx, e_lse, errs)
 
 
+@pytest.mark.parametrize("dh,slope", [(128, 0.02), (128, 0.2), (64, 0.05), (64, 1.0)])
+def test_attention_forward_with_steadily_rising_scores(dh, slope):
+    """Scores that grow with the key index, slowly or fast: the running maximum keeps moving, so the
+    forward kernel's lazily updated reference point is exercised both ways (probabilities above 1
+    between updates at the small slopes; an update in every tile at the large ones)."""
+    B, S, H = 1, 1024, 2
+    Hd = H * dh
+    rng = np.random.default_rng(int(1000 * slope) + dh)
+    u = rng.standard_normal(dh); u /= np.linalg.norm(u)
+    qkv = 0.3 * rng.standard_normal((B, S, 3 * Hd))
+    ramp = slope * np.arange(S)[:, None] * np.sqrt(dh)            # score of (i, j) gains slope * j
+    for h in range(H):
+        qkv[0, :, h * dh:(h + 1) * dh] += u                       # q_i . u = 1 (+ noise)
+        qkv[0, :, Hd + h * dh:Hd + (h + 1) * dh] += ramp * u      # k_j . u = slope * j * sqrt(dh)
+    qkv = _store(qkv, "bf16")
+    ctx_ref, lse_ref = orc.attention_fwd(qkv, H, dh)
+    qd = to_dev(qkv, "bf16")
+    ctx = torch.empty((B, S, Hd), dtype=torch.bfloat16, device=DEV); lse = torch.empty((B, H, S), device=DEV)
+    fax.fax_attention_fwd(fax.FAX_BF16, B, S, H, dh, qd, ctx, lse, fax.PATH_MFMA)
+    assert err(to_np(ctx), ctx_ref, "bf16") <= 8e-3
+    assert np.abs(to_np(lse) - lse_ref).max() <= 2e-4 * max(1.0, np.abs(lse_ref).max())
+
+
 def test_attention_mfma_rejects_uncovered_shapes():
     q = torch.zeros((1, 100, 3 * 64), dtype=torch.bfloat16, device=DEV)
     with pytest.raises(fax.FaxError) as e:
