@@ -201,7 +201,8 @@ __device__ __forceinline__ void pair_of_tiles(int n_tiles, int BH, int& pair, in
 //   * skew: the vector work of half u rides slot by slot on the MFMAs of its neighbours within
 //     the same wave (three LDS buffers, two sets of score registers);
 //   * occupancy: keep the kernel within the register budget of two waves per SIMD and the LDS
-//     budget of two workgroups per CU and let the hardware interleave two workgroups' phases.
+//     budget of two workgroups per CU and let the hardware interleave two workgroups' phases
+//     (a wave raises its priority for its MFMA phases, so the matrix core is fed first: -4 %).
 // Occupancy won wherever the kernel fits (forward 208 -> 167 us and dQ 261 -> 217 us at dh = 128,
 // dK/dV 13.2 -> 11.2 ms over the 124M model's twelve layers at dh = 64; the skewed forward and dQ
 // kernels were 4-20 % slower than these and are gone).  dK/dV at dh = 128 holds 192 registers of
@@ -277,6 +278,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int
 #pragma unroll
         for (int v = 0; v < 16; v++) s[jt][v] = 0.f;
       __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int i = 0; i < N; i++) {
         s[i % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], qf[i / 2], s[i % 2], 0, 0, 0);
@@ -285,6 +287,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int
         if (i < 2 * NSEG) tile_load(j0n, (t + 1) & 1, i);
         __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_s_setprio(0);
       // Scores stay unscaled; the softmax scale rides in the exponent: p = 2^(c s - c m), c = scale log2 e.
       if (MASK) {
 #pragma unroll
@@ -330,6 +333,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int
       rs = sum32(rs);
       l += rs;
       __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int i = 0; i < N; i++) {
         const int dt = i % DT;
@@ -337,6 +341,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int
         if (i + LEAD < N) fc[i % LEAD] = col_frag(i + LEAD);
         __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_s_setprio(0);
       lds_dma_wait();
       __syncthreads();
     };
@@ -445,6 +450,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
         f32x16 sc, dp;
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int i = 0; i < N1; i++) {
           const int ks = i / 2;
@@ -456,6 +462,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
           __builtin_amdgcn_sched_barrier(0);
         }
         bf16x8 db[2];
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           float p = __builtin_amdgcn_exp2f(fmaf(sc[v], c, -li));
@@ -463,6 +470,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
           db[v >> 3][v & 7] = (__bf16)(p * (dp[v] - di));
         }
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int i = 0; i < N3; i++) {
           dq[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], db[i / DT], dq[i % DT], 0, 0, 0);
@@ -470,6 +478,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+      __builtin_amdgcn_s_setprio(0);
       lds_dma_wait();
       __syncthreads();
     };
@@ -759,6 +768,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_phased_mfma_kernel(int S,
       for (int it = 0; it < 2; it++) {
         const int i0h = i_first + t * TR + it * 32;  // first query of the half
         f32x16 sc, dp;
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int i = 0; i < N; i++) {
           if (i % 2 == 0) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % LEAD], kf[i / 2], i < 2 ? zero : sc, 0, 0, 0);
@@ -769,6 +779,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_phased_mfma_kernel(int S,
           __builtin_amdgcn_sched_barrier(0);
         }
         bf16x8 pb[2], db[2];
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int q = 0; q < 4; q++) {
           const float4 l4 = stat4(it, q, 0), d4 = stat4(it, q, 1);
@@ -783,6 +794,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_phased_mfma_kernel(int S,
           }
         }
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int i = 0; i < N; i++) {
           const int hh = i / (2 * DT), dt = (i / 2) % DT;
@@ -793,6 +805,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_phased_mfma_kernel(int S,
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+      __builtin_amdgcn_s_setprio(0);
       lds_dma_wait();
       __syncthreads();
     };
