@@ -214,7 +214,7 @@ __device__ __forceinline__ void pair_of_tiles(int n_tiles, int BH, int& pair, in
 // softmax over the 64 keys, P3 = O^T += V^T P^T.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ ctx, float* __restrict__ lse) {
   constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
   constexpr int N = 2 * KS;            // MFMAs per phase (P3: 2 halves x 2 k-steps x DT = 2 KS as well)
