@@ -20,8 +20,8 @@ struct AttnCost {
   double fwd, dq, dkv;
 };
 static AttnCost attn_cost(int dh, int S, int dtype) {
-  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 128) return {0.62, 0.89, 1.49};
-  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 64) return {0.37, 0.44, 0.66};
+  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 128) return {0.59, 0.84, 1.48};
+  if (dtype == FAX_BF16 && S % 128 == 0 && dh == 64) return {0.32, 0.42, 0.63};
   const double c = 0.25 * dh;  // the scalar kernels: a few TFLOP/s
   return {c, 2 * c, 2 * c};
 }
