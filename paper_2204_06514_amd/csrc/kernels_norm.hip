@@ -482,9 +482,15 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
   if (D % VN == 0 && nvec <= 256 * LN_MAXV) {
     // one pass: dx and, per workgroup, a partial row of dgamma and of dbeta
     int parts;
-    // at least eight row blocks per workgroup: each workgroup writes two partial rows, which would
-    // otherwise rival the traffic of the rows themselves when there are few tokens
-    auto grid = [&](int rpb) { return parts = max(1, min(LN_BWD_PARTS, (rows + 8 * rpb - 1) / (8 * rpb))); };
+    // Each workgroup writes two fp32 partial rows, which the fold reads back: with R rows per
+    // workgroup that is 2 / R on top of the rows' own traffic.  Eight row blocks per workgroup, fewer
+    // (down to two) while that leaves less than two workgroups per CU: with few tokens the
+    // parallelism is worth more than the partial rows cost (2048 x 5120: 43 -> 31 us).
+    auto grid = [&](int rpb) {
+      int per_wg = 8;
+      while (per_wg > 2 && rows / (per_wg * rpb) < 512) per_wg /= 2;
+      return parts = max(1, min(LN_BWD_PARTS, (rows + per_wg * rpb - 1) / (per_wg * rpb)));
+    };
     // threads per row and vectors per thread: as few registers as the row length allows, so that
     // several workgroups fit on a CU
 #define FAX_LN_BWD_FUSED(TPR, NV)                                                                                   \
@@ -493,7 +499,10 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
     if (nvec <= 64 * 2) FAX_LN_BWD_FUSED(64, 2);
     else if (nvec <= 64 * 4) FAX_LN_BWD_FUSED(64, 4);
     else if (nvec <= 256 * 2) FAX_LN_BWD_FUSED(256, 2);
+    else if (nvec <= 256 * 3) FAX_LN_BWD_FUSED(256, 3);
     else if (nvec <= 256 * 4) FAX_LN_BWD_FUSED(256, 4);
+    else if (nvec <= 256 * 5) FAX_LN_BWD_FUSED(256, 5);
+    else if (nvec <= 256 * 6) FAX_LN_BWD_FUSED(256, 6);
     else FAX_LN_BWD_FUSED(256, LN_MAXV);
 #undef FAX_LN_BWD_FUSED
     FAX_LAUNCH_CHECK("ln_bwd_fused");

@@ -91,7 +91,8 @@ def test_gemm_auto_path_falls_back_on_ragged_shapes():
                                           ("bf16", 17, 20000),
                                           # every lanes-per-row x vectors-per-thread form of the one-pass backward,
                                           # and a workgroup that walks over many row blocks with a ragged last one
-                                          ("bf16", 70, 2048), ("f32", 50, 768), ("bf16", 20, 8192), ("bf16", 5001, 768)])
+                                          ("bf16", 70, 2048), ("f32", 50, 768), ("bf16", 20, 8192), ("bf16", 5001, 768),
+                                          ("bf16", 19, 5120), ("bf16", 23, 10240), ("bf16", 2048, 1024)])
 def test_layernorm_forward_backward(dtype, rows, D):
     rng = np.random.default_rng(rows + D)
     x = _store(rng.standard_normal((rows, D)) * 2 + 0.5, dtype)
