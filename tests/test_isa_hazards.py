@@ -1,6 +1,6 @@
-"""CPU-only checks of the generated GEMM code.
+"""CPU-only checks of the generated GEMM and attention code.
 
-The main loop issues its slab loads through inline assembly (direct global -> LDS loads), which
+The GEMM main loop issues its slab loads through inline assembly (direct global -> LDS loads), which
 the compiler knows nothing about: it neither counts them in its own waits nor knows which
 registers they occupy.  Two things therefore have to hold in the emitted gfx950 assembly:
 
@@ -13,7 +13,9 @@ registers they occupy.  Two things therefore have to hold in the emitted gfx950 
     (the A slab just requested, which no wave reads before a later barrier: 8 instructions at
     256-row tiles, 4 at 128-row tiles), and the program never ends with any in flight.
 
-Compiler-issued loads are the compiler's own business and are not modelled here."""
+The attention kernels load their tiles the same way and wait for all of them before every barrier
+(allowed in flight: none).  Compiler-issued loads are the compiler's own business and are not
+modelled here."""
 import os
 import re
 import shutil
@@ -23,18 +25,21 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "paper_2204_06514_amd", "csrc", "kernels_gemm_mfma.hip")
+SRC_ATTN = os.path.join(ROOT, "paper_2204_06514_amd", "csrc", "kernels_attn_mfma.hip")
 
-ASM_ALLOWED = ("s_mov_b32 m0", "s_nop", "global_load_lds_dwordx4", "s_waitcnt", "s_barrier")
+ASM_ALLOWED = ("s_mov_b32 m0", "s_nop", "global_load_lds_dword", "s_waitcnt", "s_barrier")
 
 
-def scan(asm_text):
+def scan(asm_text, kernel_re=r"_ZN3fax16gemm_mfma_kernel"):
     """-> (kernels scanned, {kernel: [problems]})"""
-    kernels = re.split(r"\n(?=_ZN3fax16gemm_mfma_kernel[^\n]*:\s)", asm_text)
+    kernels = re.split(r"\n(?=" + kernel_re + r"[^\n]*:\s)", asm_text)
     bad = {}
     for k in kernels[1:]:
         name = k.split(":")[0]
         problems, in_asm, in_flight = [], False, 0
-        allowed = 8 if "ILi256ELi" in name else 4   # the A slab: 8 load instructions per wave at 256 rows, 4 at 128
+        # GEMM, the A slab: 8 load instructions per wave at 256 rows, 4 at 128; attention: nothing
+        allowed = 0 if "attn" in name else 8 if "ILi256ELi" in name else 4
+        jumps, fell_through = {}, True   # label -> most loads in flight at a jump to it seen so far
         for ln in k.split("s_endpgm")[0].split("\n") + ["s_endpgm"]:
             if "#ASMSTART" in ln:
                 in_asm = True
@@ -43,7 +48,22 @@ def scan(asm_text):
                 in_asm = False
                 continue
             ln = ln.split(";")[0].strip()
+            if ln.startswith(".LBB") and ln.endswith(":"):
+                # a block entered only by jumps from above inherits their count, not that of the
+                # block laid out before it (which left with an unconditional branch)
+                seen = jumps.get(ln[:-1])
+                if fell_through:
+                    in_flight = max(in_flight, seen or 0)
+                elif seen is not None:
+                    in_flight = seen
+                fell_through = True
+                continue
             if not ln or ln.endswith(":") or ln.startswith("."):
+                continue
+            m = re.match(r"s_c?branch\w*\s+(\.LBB\w+)", ln)
+            if m:
+                jumps[m.group(1)] = max(jumps.get(m.group(1), 0), in_flight)
+                fell_through = not ln.startswith("s_branch")
                 continue
             if in_asm and not ln.startswith(ASM_ALLOWED):
                 problems.append("in asm block: " + ln)
@@ -76,19 +96,36 @@ def test_scanner_catches_planted_mistakes():
     assert "in flight at s_endpgm" in scan(no_drain)[1][name][0]
     reg_load = head + " ;;#ASMSTART\n global_load_dwordx4 v[4:7], v[0:1], off\n ;;#ASMEND\n s_endpgm\n"
     assert "in asm block" in scan(reg_load)[1][name][0]
+    # a block after an unconditional branch counts what the jumps to it carry, not what precedes it in the layout
+    tail_ok = head + " s_cbranch_scc1 .LBB0_9\n" + dma * 3 + " s_branch .LBB0_1\n.LBB0_9:\n s_endpgm\n"
+    assert scan(tail_ok) == (1, {})
+    tail_bad = head + dma * 2 + " s_cbranch_scc1 .LBB0_9\n s_branch .LBB0_1\n.LBB0_9:\n s_endpgm\n"
+    assert "2 LDS loads possibly in flight at s_endpgm" in scan(tail_bad)[1][name][0]
     m0_clobber = head + " s_mov_b32 m0, -1\n s_endpgm\n"
     assert "m0 used outside" in scan(m0_clobber)[1][name][0]
 
 
-def test_direct_to_lds_loads_are_waited_for(tmp_path):
+def _assembly(tmp_path, src, extra=()):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(hipcc):
         pytest.skip("hipcc not available")
-    out = tmp_path / "gemm.s"
+    out = tmp_path / "kernels.s"
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics", "-Xclang",
-           "-target-feature", "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", str(out), SRC]
+           "-target-feature", "-Xclang", "-packed-fp32-ops", *extra, "-I", os.path.join(ROOT, "include"), "-S",
+           "--cuda-device-only", "-o", str(out), src]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
-    n, bad = scan(out.read_text())
+    return out.read_text()
+
+
+def test_direct_to_lds_loads_are_waited_for(tmp_path):
+    n, bad = scan(_assembly(tmp_path, SRC))
     assert n >= 60, n
+    assert not bad, {k: v[:3] for k, v in bad.items()}
+
+
+def test_attention_tile_loads_are_waited_for(tmp_path):
+    text = _assembly(tmp_path, SRC_ATTN, ("-mllvm", "-amdgpu-mfma-vgpr-form=1"))
+    n, bad = scan(text, r"_ZN3fax\d+attn_\w+")
+    assert n >= 6, n   # forward and dQ at two head widths, one dK/dV kernel for each width
     assert not bad, {k: v[:3] for k, v in bad.items()}
