@@ -27,186 +27,13 @@
 //
 // No atomics: dQ has one writer per query row, dK/dV one writer per key row; S and dP are
 // recomputed in both backward kernels (7 tile products instead of 5).
-#include <type_traits>
-
-#include "fax_internal.h"
+#include "attn_mfma_common.h"
 
 namespace fax {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short short4v;
-typedef __attribute__((ext_vector_type(8))) short short8v;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-template <int V> using I = std::integral_constant<int, V>;
-using T_ = std::true_type;
-using F_ = std::false_type;
-
-static constexpr float LOG2E = 1.4426950408889634f;
-static constexpr int TR = 64;  // rows per LDS tile
-static constexpr float MAX_LAG = 8.f;  // forward: octaves the running maximum may rise above the exponent's reference point
-
-template <int DH>
-__device__ __forceinline__ int swz(int row) {
-  const int f = ((row & 3) << 1) | ((row >> 2) & 1);
-  return DH >= 128 ? f | (row & 8) : f;  // 16 chunks per row: 16 consecutive rows in 16 distinct chunks
-}
-
-template <int DH>
-__device__ __forceinline__ int tile_off(int row, int chunk) {
-  return row * (DH * 2) + ((chunk ^ swz<DH>(row)) << 4);
-}
-
-// A 64 x DH tile moved global -> LDS directly (global_load_lds_dwordx4: no staging registers, no
-// LDS store instructions).  One wave instruction fills 1024 consecutive LDS bytes, lane i at
-// +16 i, so the swizzle is applied on the global side: the lane that owns physical chunk p of
-// row r fetches logical chunk p ^ f(r).  lds_dma_wait() must precede the barrier that publishes
-// the tile.
-template <int DH>
-__device__ __forceinline__ void tile_dma(unsigned lds, const bf16_t* __restrict__ src, size_t ld) {
-  constexpr int NCH = DH / 8;         // 16-byte chunks per row
-  constexpr int RPI = 64 / NCH;       // rows per wave instruction
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < DH / 32; i++) {
-    const int seg = wave * (DH / 32) + i;  // which 1 KB segment of the tile
-    const int row = seg * RPI + lane / NCH;
-    const int chunk = (lane % NCH) ^ swz<DH>(row);
-    lds_dma16(src + (size_t)row * ld + chunk * 8, lds + seg * 1024u);
-  }
-}
-
-// The two fragment readers below are called with compile-time tile coordinates.  Their addresses
-// are written as (one per-lane value, the same for every call) XOR (a constant) + (a constant):
-// the swizzle only involves row bits 0..3 and chunk bits, which the tile coordinates (multiples of
-// 16 rows, whole k-steps, 32-column blocks) enter without carries.  Spelled as tile_off(row, chunk)
-// per call, each coordinate pair is a separate loop-invariant vector value to the compiler: some
-// fifty registers per kernel, more than the register budget of two waves per SIMD leaves.
-
-// A operand, rows rb..rb+31 of the tile (rb a multiple of 16), contraction over the tile's columns
-// (k-step ks).
-template <int DH>
-__device__ __forceinline__ bf16x8 frag_rows(const char* lds, int rb, int ks, int lane) {
-  const int l31 = lane & 31;
-  const unsigned lane_part = l31 * (DH * 2) + (((lane >> 5) ^ swz<DH>(l31)) << 4);  // tile_off(l31, lane >> 5)
-  const unsigned off = (lane_part ^ (unsigned)(ks << 5)) + (unsigned)(rb * (DH * 2));  // tile_off(rb + l31, 2 ks + (lane >> 5))
-  const uint4 v = *reinterpret_cast<const uint4*>(lds + off);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// A operand = transpose of the tile: output rows are tile columns cb..cb+31 (cb a multiple of 32),
-// contraction over tile rows r0 + {0..3, 8..11} + 4 g (r0 a multiple of 16; the k-slot order
-// described in the header).
-template <int DH>
-__device__ __forceinline__ bf16x8 frag_cols(const char* lds, int cb, int r0, int lane) {
-  const int blk = lane >> 4, i = lane & 15;
-  const int rl = (blk >> 1) * 4 + (i >> 2);        // row within the group of 16
-  const int cl = (blk & 1) * 16 + (i & 3) * 4;     // column within the block of 32
-  const unsigned lane_part = rl * (DH * 2) + (((cl >> 3) ^ swz<DH>(rl)) << 4) + ((cl >> 2) & 1) * 8;
-  const unsigned x = lane_part ^ (unsigned)((cb >> 3) << 4);
-  typedef __attribute__((address_space(3))) short4v lds_s4;
-  const char* p0 = lds + x + (unsigned)(r0 * (DH * 2));
-  // eight rows further down: row bit 3 flips, and with it (at 16 chunks per row) chunk bit 3
-  const char* p1 = lds + (x ^ (DH >= 128 ? 0x80u : 0u)) + (unsigned)((r0 + 8) * (DH * 2));
-  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)p0);
-  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)p1);
-  const short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int h) {
-  bf16x8 r;
-#pragma unroll
-  for (int e = 0; e < 8; e++) r[e] = (__bf16)a[h * 8 + e];
-  return r;
-}
-
-// Combine a value across lanes l and l ^ 32 (the two lanes that share a row of a 32x32 MFMA tile).
-// v_permlane32_swap hands every lane both values through the vector ALU; a shuffle would go
-// through LDS and, being returned in order with the fragment reads in flight, wait for all of them.
-__device__ __forceinline__ float max32(float v) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float sum32(float v) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// The tiles arrive through inline-assembly loads that the compiler does not count.  A value it
-// loads itself before the main loop and first uses inside it makes the compiler put its own
-// "at most N loads outstanding" wait inside the loop, which then also waits for the tile loads
-// issued a moment earlier, every iteration.  Passing such values through here forces that wait to
-// happen once, before the loop.
-template <typename T>
-__device__ __forceinline__ void settle(T& v) { asm volatile("" : "+v"(v)); }
-
-// Store a transposed 32(d) x 32(row) accumulator set: lane owns one row, DH/32 tiles of 16 d's.
-template <int DH>
-__device__ __forceinline__ void store_rows(bf16_t* __restrict__ dst, const f32x16 (&acc)[DH / 32], float mul, int g) {
-#pragma unroll
-  for (int dt = 0; dt < DH / 32; dt++)
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      bf16x4 o;
-#pragma unroll
-      for (int r = 0; r < 4; r++) o[r] = (__bf16)(acc[dt][q * 4 + r] * mul);
-      *reinterpret_cast<bf16x4*>(dst + dt * 32 + q * 8 + g * 4) = o;
-    }
-}
-
-// Segment i of this wave's share of a 64 x DH tile (see tile_dma above), as one load instruction:
-// wave-uniform tile address in scalar registers plus a per-lane byte offset that depends only on
-// the lane, the segment and the row stride, so the compiler computes it once per kernel and a load
-// costs no vector arithmetic.  `wave` must be wave-uniform (readfirstlane).
-template <int DH>
-__device__ __forceinline__ void tile_dma_seg(unsigned lds, const bf16_t* __restrict__ src, size_t ld, int wave, int i) {
-  constexpr int NCH = DH / 8, RPI = 64 / NCH;
-  const int lane = threadIdx.x & 63;
-  const int seg = wave * (DH / 32) + i;
-  const int row = seg * RPI + lane / NCH;
-  const int chunk = (lane % NCH) ^ swz<DH>(row);
-  lds_dma16(src, (unsigned)(((size_t)row * ld + chunk * 8) * sizeof(bf16_t)), lds + seg * 1024u);
-}
-
-// Workgroup -> (pair of 128-row tiles, batch-head) for the three kernels.  Under the causal mask
-// row tile r of the forward / dQ kernels meets r + 1 key blocks and key tile r of the dK/dV
-// kernel meets n - r query blocks, so tiles p and n - 1 - p are done by one workgroup, one after
-// the other: every workgroup then has the same amount of work and the grid drains without a
-// ragged tail.  Consecutive workgroup ids go to different XCDs; all workgroups of one
-// (batch, head) are dealt to the same XCD so that its K/V (Q/dO) stay in that XCD's L2.
-__device__ __forceinline__ void pair_of_tiles(int n_tiles, int BH, int& pair, int& bh) {
-  const int n_pair = (n_tiles + 1) / 2;
-  if (BH % 8 == 0) {
-    const int slot = blockIdx.x / 8;
-    bh = (slot / n_pair) * 8 + blockIdx.x % 8;
-    pair = slot % n_pair;
-  } else {
-    bh = blockIdx.x / n_pair;
-    pair = blockIdx.x % n_pair;
-  }
-}
-
-// The work on one block of keys (queries) is laid out by hand as three phases,
-//   P1  MFMAs that produce scores (row fragments of the streamed tiles from LDS)
-//   V   the vector work on the scores
-//   P3  MFMAs that consume the packed probabilities (transpose-read fragments)
-// and inside P1 and P3 every MFMA is followed by the LDS read of a fragment needed LEAD MFMAs
-// later (sched_barrier pins that order), so the matrix core does not wait for an LDS round trip.
-// P1's last reads fetch P3's first fragments; P3's last reads fetch the next P1's first rows.
-// MFMAs that accumulate into the same registers are kept at least two slots apart.
-//
-// Within one wave the three phases use different units (matrix core and LDS, vector unit, matrix
-// core and LDS) one after the other.  Two ways of filling the idle ones were built and measured:
-//   * skew: the vector work of half u rides slot by slot on the MFMAs of its neighbours within
-//     the same wave (three LDS buffers, two sets of score registers);
-//   * occupancy: keep the kernel within the register budget of two waves per SIMD and the LDS
-//     budget of two workgroups per CU and let the hardware interleave two workgroups' phases
-//     (a wave raises its priority for its MFMA phases, so the matrix core is fed first: -4 %).
-// Occupancy won wherever the kernel fits (forward 208 -> 167 us and dQ 261 -> 217 us at dh = 128,
-// dK/dV 13.2 -> 11.2 ms over the 124M model's twelve layers at dh = 64; the skewed forward and dQ
-// kernels were 4-20 % slower than these and are gone).  dK/dV at dh = 128 holds 192 registers of
-// accumulators and B operands alone and stays a one-wave-per-SIMD kernel with the skew.
+// dK, dV at DH = 128: kernels_attn_dkv128.hip (compiled with other code-generation options)
+int attn_bwd_dkv128_mfma(int B, int S, int H, const bf16_t* qkv, const float* lse, const float* delta, const bf16_t* dctx,
+                         bf16_t* dqkv, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------------
 // Forward.  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
@@ -496,194 +323,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(int S, int H, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK, dV (used for DH = 128).  Wave w owns keys 128 kt + 32 w .. + 31, held in registers as the B operands; 64-query
-// tiles of Q and dO (plus their lse and delta) stream through three LDS buffers, starting at the
-// diagonal.  Per 32-query half u:
-//   S(u) = Q K^T and dP(u) = dO V^T, alternating (row fragments of Q and dO)
-//   V(u): P = 2^(c S - lse log2 e), dS = P (dP - delta), both packed to bf16
-//   P3(u): dV^T += dO^T P and dK^T += Q^T dS, alternating (transpose-read fragments)
-// The vector work is about as long as one of the MFMA phases, so it is hidden behind the score
-// MFMAs of the *next* half: the loop body is
-//   C(u)  = slot by slot: one MFMA of S/dP(u+1), one fragment read, one element of V(u)
-//   P3(u) = slot by slot: one MFMA of dV/dK(u), one fragment read (the tile loads ride here too)
-// with two sets of score accumulators taking turns.  Past the last half the "next" scores are
-// computed from the last half again and dropped, which keeps the loop body free of special cases.
-// One barrier per tile, before P3 of the tile's first half: it publishes the next tile (first
-// needed by the row prefetch at the end of that P3) and frees the buffer of the previous one,
-// into which the tile after next is then requested.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float f4_get(const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; }
-
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(int S, int H, int BH, const bf16_t* __restrict__ qkv,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ delta,
-                                                                const bf16_t* __restrict__ dctx,
-                                                                bf16_t* __restrict__ dqkv) {
-  constexpr int KS = DH / 16, DT = DH / 32, TB = TR * DH * 2;
-  // Q tile | dO tile | per wave w: lse[16 w .. +15], delta[16 w .. +15], and a copy of both (the
-  // 64 lanes of one 4-byte load instruction: 32 useful values, fetched twice)
-  constexpr int LD_OFF = 2 * TB, STAGE = 2 * TB + 4 * 256, NBUF = 3;
-  constexpr int N = 2 * KS;                   // MFMAs per phase
-  constexpr int LEAD = N < 8 ? N : 8;         // fragments in flight
-  constexpr int NSEG = DH / 32;               // 1 KB load instructions per wave per tile and operand
-  constexpr int EPS = 16 / N;                 // score elements per slot of C
-  static_assert(16 % N == 0 && 2 * NSEG + 1 <= N && 8 <= N, "slot plan");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n_kt = S / 128;
-  int pair, bh;
-  pair_of_tiles(n_kt, BH, pair, bh);
-  const int b = bh / H, h = bh % H;
-  const int Hd = H * DH;
-  const size_t ld = 3 * (size_t)Hd;
-  const bf16_t* base = qkv + (size_t)b * S * ld + h * DH;
-  const bf16_t* dob = dctx + (size_t)b * S * Hd + h * DH;
-  const float* lrow = lse + ((size_t)b * H + h) * S;
-  const float* drow = delta + ((size_t)b * H + h) * S;
-  const int lane = threadIdx.x & 63, g = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const float c = rsqrtf((float)DH) * LOG2E;
-  const unsigned sm = lds_addr(smem);
-
-  for (int pass = 0; pass < 2; pass++) {
-    const int kt = pass == 0 ? pair : n_kt - 1 - pair;
-    if (pass == 1 && kt == pair) break;  // odd number of key tiles: the middle one stands alone
-    const int j0w = kt * 128 + wave * 32, jk = j0w + (lane & 31);
-    bf16x8 kf[KS], vf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + Hd + ks * 16 + g * 8));
-      vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (size_t)jk * ld + 2 * Hd + ks * 16 + g * 8));
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) { settle(kf[ks]); settle(vf[ks]); }
-    f32x16 dk[DT], dv[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) dk[dt][v] = dv[dt][v] = 0.f;
-
-    const int i_first = kt * 128;
-    const int n_q = (S - i_first) / TR, n_half = 2 * n_q;
-    // Tile of queries i0.. into buffer `buf`, one load instruction per call: this wave's NSEG
-    // segments of Q (i < NSEG), of dO (i < 2 NSEG), and its 16 lse and 16 delta values.
-    auto tile_load = [&](int i0, int buf, int i) {
-      const unsigned st = sm + buf * STAGE;
-      if (i < NSEG) tile_dma_seg<DH>(st, base + (size_t)i0 * ld, ld, wave, i);
-      else if (i < 2 * NSEG) tile_dma_seg<DH>(st + TB, dob + (size_t)i0 * Hd, (size_t)Hd, wave, i - NSEG);
-      else lds_dma4(((lane & 16) ? drow : lrow) + i0 + wave * 16 + (lane & 15), st + LD_OFF + wave * 256);
-    };
-    auto stage = [&](int t) { return smem + (min(t, n_q - 1) % NBUF) * STAGE; };  // past the end: the last tile again
-    auto row_frag = [&](const char* st, int it, int i) { return frag_rows<DH>(i % 2 ? st + TB : st, it * 32, i / 2, lane); };
-    auto col_frag = [&](const char* st, int it, int i) {
-      return frag_cols<DH>(i % 2 ? st : st + TB, ((i / 2) % DT) * 32, it * 32 + (i / (2 * DT)) * 16, lane);
-    };
-    // lse / delta of the rows 32 it + 8 q + 4 g + 0..3 that this lane meets in accumulator group q
-    auto stat4 = [&](const char* st, int it, int q, int which) {
-      const int row = it * 32 + q * 8 + g * 4;
-      return *reinterpret_cast<const float4*>(st + LD_OFF + (row >> 4) * 256 + which * 64 + (row & 15) * 4);
-    };
-
-    bf16x8 fr[LEAD], fc[LEAD];
-    f32x16 sc[2], dp[2];  // [u & 1]: scores of half u
-    float4 l4[4], d4[4];
-    bf16x8 pb[2], db[2];
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-    // MFMA i of S/dP for the half whose row fragments are in flight, into score set `par`
-    auto score_mfma = [&](int par, int i) {
-      if (i % 2 == 0) sc[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], kf[i / 2], i < 2 ? zero : sc[par], 0, 0, 0);
-      else dp[par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % LEAD], vf[i / 2], i < 2 ? zero : dp[par], 0, 0, 0);
-    };
-    // Half u (it = u & 1 fixed at compile time): C(u), [barrier], P3(u).
-    auto step = [&](auto mask_c, auto it_c, int u) {
-      constexpr bool MASK = decltype(mask_c)::value;
-      constexpr int IT = decltype(it_c)::value;
-      const int t = u >> 1;
-      const char* st = stage(t);                    // tile of half u
-      const char* st1 = stage((u + 1) >> 1);        // ... of half u + 1
-      const char* st2 = stage(t + 1);               // ... of half u + 2
-      const int i0h = i_first + t * TR + IT * 32;   // first query of half u
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        score_mfma(IT ^ 1, i);
-        if (i + LEAD < N) fr[i % LEAD] = row_frag(st1, IT ^ 1, i + LEAD);
-        else fc[i + LEAD - N] = col_frag(st, IT, i + LEAD - N);
-#pragma unroll
-        for (int e = 0; e < EPS; e++) {
-          const int v = i * EPS + e, q = v >> 2, r = v & 3;
-          float p = __builtin_amdgcn_exp2f(fmaf(sc[IT][v], c, -LOG2E * f4_get(l4[q], r)));
-          if (MASK && jk > i0h + q * 8 + g * 4 + r) p = 0.f;
-          const float d = p * (dp[IT][v] - f4_get(d4[q], r));
-          pb[v >> 3][v & 7] = (__bf16)p;
-          db[v >> 3][v & 7] = (__bf16)d;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (IT == 0) {
-        // every load issued so far (the newest: tile t + 1) has landed; all waves are past P3 of
-        // half u - 1, the last reader of tile t - 1
-        lds_dma_wait();
-        __syncthreads();
-      }
-      const int i0n = i_first + min(t + 2, n_q - 1) * TR;
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        const int hh = i / (2 * DT), dt = (i / 2) % DT;
-        if (i % 2 == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], pb[hh], dv[dt], 0, 0, 0);
-        else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[i % LEAD], db[hh], dk[dt], 0, 0, 0);
-        if (i + LEAD < N) fc[i % LEAD] = col_frag(st, IT, i + LEAD);
-        else fr[i + LEAD - N] = row_frag(st2, IT, i + LEAD - N);
-        if (i < 8) {  // statistics of half u + 1, for the next C
-          if (i < 4) l4[i] = stat4(st1, IT ^ 1, i, 0);
-          else d4[i - 4] = stat4(st1, IT ^ 1, i - 4, 1);
-        }
-        if (IT == 0 && i <= 2 * NSEG) tile_load(i0n, (t + 2) % NBUF, i);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    };
-
-#pragma unroll
-    for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first, 0, i);
-#pragma unroll
-    for (int i = 0; i <= 2 * NSEG; i++) tile_load(i_first + TR, 1, i);
-    lds_dma_wait();
-    __syncthreads();
-    // scores of half 0, cold: fragment reads exposed once per pass
-    {
-      const char* st = stage(0);
-#pragma unroll
-      for (int i = 0; i < LEAD; i++) fr[i] = row_frag(st, 0, i);
-#pragma unroll
-      for (int q = 0; q < 4; q++) { l4[q] = stat4(st, 0, q, 0); d4[q] = stat4(st, 0, q, 1); }
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        score_mfma(0, i);
-        if (i + LEAD < N) fr[i % LEAD] = row_frag(st, 0, i + LEAD);
-        else fr[i + LEAD - N] = row_frag(st, 1, i + LEAD - N);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // the first two tiles (four halves) straddle the diagonal of this workgroup's 128 keys
-    step(T_{}, I<0>{}, 0);
-    step(T_{}, I<1>{}, 1);
-    step(T_{}, I<0>{}, 2);
-    step(T_{}, I<1>{}, 3);
-    for (int u = 4; u < n_half; u += 2) {
-      step(F_{}, I<0>{}, u);
-      step(F_{}, I<1>{}, u + 1);
-    }
-    lds_dma_wait();   // the re-requested last tile
-    __syncthreads();  // LDS is reused by the next pass
-
-    const float scale = rsqrtf((float)DH);
-    bf16_t* out = dqkv + ((size_t)b * S + jk) * ld + h * DH;
-    store_rows<DH>(out + Hd, dk, scale, g);
-    store_rows<DH>(out + 2 * Hd, dv, 1.f, g);
-  }  // pass
-}
-
-// ---------------------------------------------------------------------------------------------
 // dK, dV without the skew (used for DH = 64, where the kernel then fits the register budget of
 // two waves per SIMD and several workgroups share a CU).  The same arithmetic as the kernel above,
 // a 32-query half at a time: P1 = S and dP (2 KS MFMAs), V = P and dS packed to bf16, P3 = dV^T and
@@ -865,9 +504,7 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, cons
     hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx,
                        dqkv);
   } else {
-    constexpr size_t lds_kv = 3 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // three stages
-    FAX_TRY(set_lds(attn_bwd_dkv_mfma_kernel<DH>, lds_kv));
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx, dqkv);
+    FAX_TRY(attn_bwd_dkv128_mfma(B, S, H, qkv, lse, delta, dctx, dqkv, s));
   }
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;

@@ -26,6 +26,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "paper_2204_06514_amd", "csrc", "kernels_gemm_mfma.hip")
 SRC_ATTN = os.path.join(ROOT, "paper_2204_06514_amd", "csrc", "kernels_attn_mfma.hip")
+SRC_DKV128 = os.path.join(ROOT, "paper_2204_06514_amd", "csrc", "kernels_attn_dkv128.hip")
 
 ASM_ALLOWED = ("s_mov_b32 m0", "s_nop", "global_load_lds_dword", "s_waitcnt", "s_barrier")
 
@@ -125,7 +126,10 @@ def test_direct_to_lds_loads_are_waited_for(tmp_path):
 
 
 def test_attention_tile_loads_are_waited_for(tmp_path):
-    text = _assembly(tmp_path, SRC_ATTN, ("-mllvm", "-amdgpu-mfma-vgpr-form=1"))
+    text = _assembly(tmp_path, SRC_ATTN, ("-mllvm", "-amdgpu-mfma-vgpr-form=1"))   # options as in build.py
     n, bad = scan(text, r"_ZN3fax\d+attn_\w+")
-    assert n >= 6, n   # forward and dQ at two head widths, one dK/dV kernel for each width
+    assert n >= 5, n   # forward and dQ at two head widths, dK/dV at 64
+    assert not bad, {k: v[:3] for k, v in bad.items()}
+    n, bad = scan(_assembly(tmp_path, SRC_DKV128), r"_ZN3fax\d+attn_\w+")
+    assert n >= 1, n   # dK/dV at 128
     assert not bad, {k: v[:3] for k, v in bad.items()}
