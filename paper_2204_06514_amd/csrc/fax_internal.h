@@ -87,7 +87,10 @@ int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const floa
            void* ws, hipStream_t s);
 size_t colsum_ws_bytes(int N);
 // out[i] (+)= sum_p partial[p * n + i], p < parts, in that order
-int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s);
+// out[i] (+)= sum over p < parts of partial[p * n + i]; optionally a second stack (nb elements per part) into
+// out_b in the same launch.  Fixed summation order.
+int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s, int nb = 0,
+                  const float* partial_b = nullptr, float* out_b = nullptr);
 // out[n] (+)= sum over rows of a[r, n]; a in dtype with leading dimension lda.
 int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws,
            hipStream_t s);

@@ -774,8 +774,7 @@ int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
   else if (plan.tile_m == 256) FAX_TRY((dispatch<256, 128>(g, e, s)));
   else FAX_TRY((dispatch<128, 128>(g, e, s)));
   if (splits > 1) {
-    FAX_TRY(fold_partials(splits, mn, part_c, (float*)g0.C, g0.accumulate, s));
-    if (g0.colsum) FAX_TRY(fold_partials(splits, (size_t)g.N, part_cs, g0.colsum, g0.accumulate, s));
+    FAX_TRY(fold_partials(splits, mn, part_c, (float*)g0.C, g0.accumulate, s, g0.colsum ? g.N : 0, part_cs, g0.colsum));
   }
   return FAX_OK;
 }

@@ -424,8 +424,20 @@ __global__ __launch_bounds__(256) void fold_partials_kernel(int parts, int N, co
 }
 
 // The same for long vectors, four elements per thread: out[i] (+)= (partial[0][i] + partial[1][i] + ...).
+// The blocks from `blocks_a` on fold a second, short stack of partials (nb elements each, any nb) into out_b,
+// one element per thread, in the same launch.
 __global__ __launch_bounds__(256) void fold_partials_vec_kernel(int parts, size_t n4, const float4* __restrict__ partial,
-                                                                float4* __restrict__ out, int accumulate) {
+                                                                float4* __restrict__ out, int accumulate, unsigned blocks_a,
+                                                                int nb, const float* __restrict__ partial_b,
+                                                                float* __restrict__ out_b) {
+  if (blockIdx.x >= blocks_a) {
+    const int j = (int)(blockIdx.x - blocks_a) * 256 + (int)threadIdx.x;
+    if (j >= nb) return;
+    float sb = partial_b[j];
+    for (int p = 1; p < parts; p++) sb += partial_b[(size_t)p * nb + j];
+    out_b[j] = accumulate ? out_b[j] + sb : sb;
+    return;
+  }
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
   float4 s = partial[i];
@@ -447,15 +459,19 @@ __global__ __launch_bounds__(256) void fold_partials_vec_kernel(int parts, size_
   out[i] = s;
 }
 
-int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s) {
-  if (n == 0) return FAX_OK;
+int fold_partials(int parts, size_t n, const float* partial, float* out, bool accumulate, hipStream_t s, int nb,
+                  const float* partial_b, float* out_b) {
+  if (n == 0) return nb > 0 ? fold_partials(parts, (size_t)nb, partial_b, out_b, accumulate, s) : FAX_OK;
   if (n % 4 == 0 && n >= 4096 && ((reinterpret_cast<uintptr_t>(partial) | reinterpret_cast<uintptr_t>(out)) & 15) == 0 &&
-      n / 4 / 256 < 0x7fffffff) {
-    hipLaunchKernelGGL(fold_partials_vec_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s, parts, n / 4,
-                       (const float4*)partial, (float4*)out, accumulate ? 1 : 0);
+      n / 4 / 256 < 0x7ff00000) {
+    const unsigned blocks_a = (unsigned)((n / 4 + 255) / 256);
+    const unsigned blocks_b = nb > 0 ? (unsigned)((nb + 255) / 256) : 0u;
+    hipLaunchKernelGGL(fold_partials_vec_kernel, dim3(blocks_a + blocks_b), dim3(256), 0, s, parts, n / 4,
+                       (const float4*)partial, (float4*)out, accumulate ? 1 : 0, blocks_a, nb, partial_b, out_b);
     FAX_LAUNCH_CHECK("fold_partials");
     return FAX_OK;
   }
+  if (nb > 0) FAX_TRY(fold_partials(parts, (size_t)nb, partial_b, out_b, accumulate, s));
   if (n > (size_t)0x7fffffff) {
     set_error("fold_partials: %zu elements", n);
     return FAX_ERR_UNSUPPORTED;
