@@ -56,6 +56,13 @@ enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
 /* FaxModelDims.flags */
 #define FAX_FLAG_SKIP_UPDATE 1u /* fax_train_step: stop after the gradients */
 #define FAX_FLAG_ACCUMULATE 2u  /* fax_train_step: add this call's gradients to `grads` instead of overwriting */
+/* fax_train_step: no floating-point atomics anywhere.  The one kernel that uses them, the
+ * scatter-add of the token-embedding gradient (rows of equal token ids add up in the order the
+ * hardware happens to serve them), is replaced by an ordered reduction: one writer per vocabulary
+ * row, positions added in ascending order.  Every other kernel of the library already has one
+ * writer per output element and fixed-order reductions, with or without the flag: two calls on the
+ * same inputs then return identical bits. */
+#define FAX_FLAG_DETERMINISTIC 4u
 
 /* Shape of one decoder block as one device holds it.  H and F are the LOCAL
  * head count and feed-forward width; H*dh need not equal D (a tensor-parallel
@@ -144,6 +151,20 @@ int fax_train_workspace_bytes(const FaxModelDims* dims, size_t* out);
 
 /* Host-only argument check used by every entry point; exposed for tests. */
 int fax_block_dims_check(const FaxBlockDims* dims);
+
+/* Host-only: the launch plan the library would use for a bf16 product C[M,N] = A B with a
+ * contraction of K (c_f32 != 0: the fp32-output weight-gradient form, which may split K when
+ * the caller provides scratch, as fax_block_bwd and fax_train_step do).
+ *   tail          0: one launch.  1 / 2: the last 128 rows / columns run as a launch of their own
+ *                 (a dimension that is an odd multiple of 128); tile_* and splits then describe
+ *                 the bulk.
+ *   tile_m/tile_n the tile class; 0 when no class divides the shape (the scalar kernel runs).
+ *   splits        K ranges, each writing a partial product that a fold kernel sums (1: none).
+ * Exposed so that a test can assert that a cut-down workload runs the plans of the full one. */
+typedef struct FaxGemmPlan {
+  int32_t tail, tile_m, tile_n, splits;
+} FaxGemmPlan;
+int fax_gemm_plan(int M, int N, int K, int c_f32, FaxGemmPlan* out);
 
 /*
  * Forward pass of one pre-LayerNorm decoder block (Fig. 1; forward phase of Fig. 4):
@@ -263,8 +284,10 @@ typedef struct FaxAnalysis {
 int fax_analyze(const FaxModelDims* global_dims, const FaxMesh* mesh, FaxAnalysis* out);
 
 /*
- * Building blocks, exported so each kernel can be checked and timed alone.
- * All follow the conventions above; dtype is FAX_F32 or FAX_BF16.
+ * Building blocks, exported so each kernel can be checked and timed alone: test and benchmark
+ * hooks into the steps of the four entry points above.  They follow no passage of the paper of
+ * their own (the steps they perform are those listed at fax_block_fwd / fax_block_bwd /
+ * fax_train_step) and the conventions above; dtype is FAX_F32 or FAX_BF16.
  */
 
 /* C[M,N] = op(A) op(B), fp32 accumulate.  ta = 0: A is [M,K] row-major (lda); ta = 1: A is

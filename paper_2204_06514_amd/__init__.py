@@ -21,6 +21,7 @@ FAX_GELU_TANH, FAX_GELU_ERF = 0, 1
 FAX_FLAG_TP_PARTIAL = 1
 FAX_FLAG_SKIP_UPDATE = 1
 FAX_FLAG_ACCUMULATE = 2
+FAX_FLAG_DETERMINISTIC = 4
 PATH_AUTO, PATH_SCALAR, PATH_MFMA = 0, 1, 2
 
 TENSOR_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -65,6 +66,10 @@ class FaxModelTensors(C.Structure):
                 ("blocks", C.POINTER(FaxBlockTensors))]
 
 
+class FaxGemmPlan(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tail", "tile_m", "tile_n", "splits")]
+
+
 class FaxMesh(C.Structure):
     _fields_ = [("data", C.c_int32), ("tensor", C.c_int32)]
 
@@ -93,6 +98,7 @@ def _load():
         "fax_version": (C.c_char_p, []),
         "fax_last_error": (C.c_char_p, []),
         "fax_block_dims_check": (i32, [P(FaxBlockDims)]),
+        "fax_gemm_plan": (i32, [i32, i32, i32, i32, P(FaxGemmPlan)]),
         "fax_block_saved_layout": (i32, [P(FaxBlockDims), P(FaxSavedLayout)]),
         "fax_block_bwd_layout": (i32, [P(FaxBlockDims), P(FaxBwdLayout)]),
         "fax_block_workspace_bytes": (i32, [P(FaxBlockDims), P(sz)]),
@@ -187,6 +193,13 @@ def fax_last_error():
 
 def fax_block_dims_check(dims):
     return _lib.fax_block_dims_check(C.byref(dims))
+
+
+def fax_gemm_plan(M, N, K, c_f32=0):
+    """-> (tail, tile_m, tile_n, splits): the launch plan of a bf16 product (host only)."""
+    out = FaxGemmPlan()
+    _check(_lib.fax_gemm_plan(M, N, K, int(c_f32), C.byref(out)))
+    return (out.tail, out.tile_m, out.tile_n, out.splits)
 
 
 def fax_block_saved_layout(dims):
@@ -307,3 +320,4 @@ def fax_timing_report(capacity=64):
 def fax_cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, stream=None):
     _check(_lib.fax_cross_entropy(dtype, N, V, _ptr(logits), _ptr(labels), _ptr(dlogits), _ptr(row_loss),
                                   _ptr(loss_out), _stream(stream)))
+

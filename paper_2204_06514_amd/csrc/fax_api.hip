@@ -204,6 +204,26 @@ static int check_ptr(const void* p, const char* name) {
   return FAX_OK;
 }
 
+static int check_adamw(const FaxAdamW* hp, int step) {
+  if (!hp) {
+    set_error("hp is NULL");
+    return FAX_ERR_INVALID_ARG;
+  }
+  if (step < 1) {
+    set_error("step must be >= 1, got %d", step);
+    return FAX_ERR_INVALID_ARG;
+  }
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
+    set_error("betas must lie in [0, 1)");  // beta = 1 would make the bias correction infinite
+    return FAX_ERR_INVALID_ARG;
+  }
+  if (!(hp->eps >= 0.0) || hp->lr != hp->lr || hp->wd != hp->wd) {
+    set_error("eps must be >= 0 and lr, wd must be numbers");
+    return FAX_ERR_INVALID_ARG;
+  }
+  return FAX_OK;
+}
+
 static int attention_fwd(int dtype, int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, int path,
                          hipStream_t s) {
   const bool ok = attn_mfma_supported(dtype, B, S, H, dh);
@@ -334,7 +354,7 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
 
 // ---- model ----------------------------------------------------------------------------------
 struct TrainWs {
-  size_t xs, saved, hf, muf, rstdf, logits, row_loss, dcur, dhf, blk, headsplit, total;
+  size_t xs, saved, hf, muf, rstdf, logits, row_loss, dcur, dhf, blk, headsplit, embidx, total;
   size_t x_stride, saved_stride;
 };
 
@@ -360,6 +380,7 @@ static void train_layout(const FaxModelDims& m, TrainWs* W) {
   W->dhf = take(z.T * z.D * z.es);
   W->blk = take(B.total);
   W->headsplit = take(gemm_split_ws_bytes(m.V, (int)z.D, (int)z.T));  // the embedding gradient's product may split K
+  W->embidx = take(embed_index_ws_bytes(m.V));  // first position and count per token id (FAX_FLAG_DETERMINISTIC)
   W->total = o;
 }
 
@@ -394,6 +415,15 @@ const char* fax_version(void) { return "libfax 0.1 (gfx950, HIP)"; }
 const char* fax_last_error(void) { return g_err; }
 
 int fax_block_dims_check(const FaxBlockDims* dims) { return check_dims(dims); }
+
+int fax_gemm_plan(int M, int N, int K, int c_f32, FaxGemmPlan* out) {
+  if (!out) { set_error("out is NULL"); return FAX_ERR_INVALID_ARG; }
+  if (M <= 0 || N <= 0 || K <= 0) { set_error("non-positive GEMM size %d x %d x %d", M, N, K); return FAX_ERR_INVALID_ARG; }
+  int tail = 0;
+  const GemmSplitPlan p = gemm_plan_query(M, N, K, c_f32 != 0, &tail);
+  out->tail = tail; out->tile_m = p.tile_m; out->tile_n = p.tile_n; out->splits = p.splits;
+  return FAX_OK;
+}
 
 int fax_block_saved_layout(const FaxBlockDims* dims, FaxSavedLayout* out) {
   FAX_TRY(check_dims(dims));
@@ -479,12 +509,7 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
   FAX_TRY(check_ptr(v, "v"));
   FAX_TRY(check_ptr(grad, "grad"));
   if (lowp && misaligned(lowp)) { set_error("lowp is not 16-byte aligned"); return FAX_ERR_INVALID_ARG; }
-  if (!hp) { set_error("hp is NULL"); return FAX_ERR_INVALID_ARG; }
-  if (step < 1) { set_error("step must be >= 1, got %d", step); return FAX_ERR_INVALID_ARG; }
-  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
-    set_error("betas must lie in [0, 1)");
-    return FAX_ERR_INVALID_ARG;
-  }
+  FAX_TRY(check_adamw(hp, step));
   return adamw((float*)master, (float*)m, (float*)v, (const float*)grad, lowp, n, *hp, step, (hipStream_t)stream);
 }
 
@@ -497,12 +522,7 @@ int fax_adamw_block_step(const FaxBlockDims* dims, const FaxBlockTensors* master
   FAX_TRY(check_tensors(v, "v"));
   FAX_TRY(check_tensors(grads, "grads"));
   if (lowp) FAX_TRY(check_tensors(lowp, "lowp"));
-  if (!hp) { set_error("hp is NULL"); return FAX_ERR_INVALID_ARG; }
-  if (step < 1) { set_error("step must be >= 1, got %d", step); return FAX_ERR_INVALID_ARG; }
-  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
-    set_error("betas must lie in [0, 1)");
-    return FAX_ERR_INVALID_ARG;
-  }
+  FAX_TRY(check_adamw(hp, step));
   size_t n[12];
   tensor_counts(*dims, n);
   void* const* Ms = (void* const*)tensor_list(master);
@@ -543,6 +563,7 @@ static void eval_layout(const FaxModelDims& m, EvalWs* W) {
 int fax_eval_workspace_bytes(const FaxModelDims* dims, size_t* out) {
   size_t train = 0;
   FAX_TRY(fax_train_workspace_bytes(dims, &train));  // same validation of dims
+  if (!out) { set_error("out is NULL"); return FAX_ERR_INVALID_ARG; }
   EvalWs W;
   eval_layout(*dims, &W);
   *out = W.total;
@@ -601,8 +622,7 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
     FAX_TRY(check_model_tensors(master, dims->L, "master"));
     FAX_TRY(check_model_tensors(m, dims->L, "m"));
     FAX_TRY(check_model_tensors(v, dims->L, "v"));
-    if (!hp) { set_error("hp is NULL"); return FAX_ERR_INVALID_ARG; }
-    if (step < 1) { set_error("step must be >= 1, got %d", step); return FAX_ERR_INVALID_ARG; }
+    FAX_TRY(check_adamw(hp, step));
     if (d.dtype == FAX_F32) {
       bool same = params->tok_emb == master->tok_emb && params->pos_emb == master->pos_emb &&
                   params->lnf_g == master->lnf_g && params->lnf_b == master->lnf_b;
@@ -677,12 +697,17 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
                            w + W.saved + W.saved_stride * l, w + W.dcur, grads->blocks[l], acc, w + W.blk, s));
   // embedding backward: token rows add onto the output projection's share; positions beyond S get zero
   if (!acc) FAX_TRY(fill_zero(grads->pos_emb, (size_t)dims->S_max * D * 4, s));
-  FAX_TRY(embed_bwd(d.dtype, d.B, d.S, D, tokens, w + W.dcur, (float*)grads->tok_emb, (float*)grads->pos_emb, acc, s));
+  FAX_TRY(embed_bwd(d.dtype, d.B, d.S, D, V, tokens, w + W.dcur, (float*)grads->tok_emb, (float*)grads->pos_emb, acc,
+                    (dims->flags & FAX_FLAG_DETERMINISTIC) ? w + W.embidx : nullptr, s));
   }
   if (!update) return FAX_OK;
-  Timed phase_("phase_update", WORK_BYTE, 28.0 * ((double)V * D + (double)dims->S_max * D), s);
-
   const bool lowp = d.dtype == FAX_BF16;
+  size_t n[12];
+  tensor_counts(d, n);
+  double n_params = (double)V * D + (double)dims->S_max * D + 2.0 * D;
+  for (int i = 0; i < 12; i++) n_params += (double)L * (double)n[i];
+  Timed phase_("phase_update", WORK_BYTE, (lowp ? 30.0 : 28.0) * n_params, s);
+
   AdamWQueue q(*hp, step, s);
   auto upd = [&](void* P, void* Mst, void* Mo, void* Vo, const void* G, size_t n) {
     return q.add((float*)Mst, (float*)Mo, (float*)Vo, (const float*)G, lowp ? P : nullptr, n);
@@ -691,8 +716,6 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
   FAX_TRY(upd(params->pos_emb, master->pos_emb, m->pos_emb, v->pos_emb, grads->pos_emb, (size_t)dims->S_max * D));
   FAX_TRY(upd(params->lnf_g, master->lnf_g, m->lnf_g, v->lnf_g, grads->lnf_g, (size_t)D));
   FAX_TRY(upd(params->lnf_b, master->lnf_b, m->lnf_b, v->lnf_b, grads->lnf_b, (size_t)D));
-  size_t n[12];
-  tensor_counts(d, n);
   for (int l = 0; l < L; l++) {
     void* const* P = (void* const*)tensor_list(&params->blocks[l]);
     void* const* Ms = (void* const*)tensor_list(&master->blocks[l]);

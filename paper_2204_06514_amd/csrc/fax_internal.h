@@ -74,6 +74,7 @@ struct GemmSplitPlan {
 };
 GemmSplitPlan gemm_split_plan(int M, int N, int K);
 size_t gemm_split_ws_bytes(int M, int N, int K);
+GemmSplitPlan gemm_plan_query(int M, int N, int K, bool f32_out, int* tail);
 // Predicted duration of gemm() on this shape from the same cost model (host only), microseconds.
 double gemm_time_estimate_us(int M, int N, int K, bool f32_out);
 int gemm_mfma(const GemmArgs& g, hipStream_t s);
@@ -112,9 +113,12 @@ int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* la
                   float* row_loss, float* loss_out, float grad_scale, hipStream_t s);
 int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb,
               void* x0, hipStream_t s);
-// g_tok[tokens[b,s]] += dx0[b,s] (fp32 atomics); g_pos[s] (+)= sum_b dx0[b,s]; rows of g_pos beyond S untouched.
-int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
-              bool accumulate_pos, hipStream_t s);
+// g_tok[tokens[b,s]] += dx0[b,s]; g_pos[s] (+)= sum_b dx0[b,s]; rows of g_pos beyond S untouched.
+// index_ws = NULL: fp32 atomics (the order of the additions into a row is the hardware's).
+// index_ws = embed_index_ws_bytes(V) bytes of scratch: one writer per row, positions in ascending order.
+size_t embed_index_ws_bytes(int V);
+int embed_bwd(int dtype, int B, int S, int D, int V, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
+              bool accumulate_pos, void* index_ws, hipStream_t s);
 // Up to ADAM_BATCH tensors per launch.  add() queues a tensor (launching what is queued when the
 // batch is full), flush() launches the rest; nothing is kept beyond flush().
 constexpr int ADAM_BATCH = 16;

@@ -519,8 +519,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// Both heuristics are written for the 256 CUs of the MI355X (no device query: workspace sizes are
-// computed on hosts without a GPU too).
+// Both heuristics are written for the 256 CUs of the MI355X.  No device query here on purpose:
+// plans decide workspace sizes, and those are computed on hosts without a GPU too (the launch
+// itself sizes its grid from the device's own CU count, see launch_mfma).
 static constexpr int kCUs = 256;
 
 // Tile classes of the kernel, largest first, and what a workgroup pays per 64-wide K slab and per
@@ -597,6 +598,16 @@ static int tail_dim(int M, int N) {
   if (M % 256 == 128 && fills(M - 128, N)) return 1;
   if (N % 256 == 128 && fills(M, N - 128)) return 2;
   return 0;
+}
+
+// What gemm_mfma() does with a densely stored product, for inspection from the host: the strip
+// decomposition (0, or 1 / 2 = last 128 rows / columns apart) and the plan of the bulk.
+GemmSplitPlan gemm_plan_query(int M, int N, int K, bool f32_out, int* tail) {
+  const int td = tail_dim(M, N);
+  *tail = td;
+  if (td == 1) return plan_tiles(M - 128, N, K, f32_out, f32_out);
+  if (td == 2) return plan_tiles(M, N - 128, K, f32_out, false);  // the strip keeps C's leading dimension: no split
+  return plan_tiles(M, N, K, f32_out, f32_out);
 }
 
 // partial products, then partial column sums

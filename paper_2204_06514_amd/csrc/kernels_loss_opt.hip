@@ -177,19 +177,114 @@ int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void*
   return FAX_OK;
 }
 
-int embed_bwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
-              bool accumulate_pos, hipStream_t s) {
+// Ordered variant of the token scatter (no floating-point atomics).  Two integer tables over the
+// vocabulary are built first: first[v] = the smallest position holding token v, count[v] = how many
+// positions hold it (integer min and add commute, so the tables do not depend on the order in
+// which the atomics are served).  Then one workgroup per position: the workgroup of first[v] owns
+// row v of the gradient and adds the rows of dx0 of all count[v] positions in ascending order.
+// It finds them by walking the token array from its own position on in windows of 1024: every
+// thread compares four ids and marks its matches in a 1024-bit map in LDS, and the set bits are
+// then taken in ascending order by all threads alike.  Columns: a thread keeps EMB_ACC running sums
+// (columns tid, tid + 256, ...); rows wider than 256 * EMB_ACC take several passes over the list.
+static constexpr int EMB_ACC = 8;
+static constexpr int EMB_WIN = 1024;
+
+__global__ __launch_bounds__(256) void embed_index_init_kernel(int V, int* __restrict__ first, int* __restrict__ count) {
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v < V) {
+    first[v] = 0x7fffffff;
+    count[v] = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void embed_index_kernel(int T, const int32_t* __restrict__ tokens, int* __restrict__ first,
+                                                          int* __restrict__ count) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < T) {
+    const int v = tokens[t];
+    atomicMin(first + v, t);
+    atomicAdd(count + v, 1);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_tok_ordered_kernel(int Tn, int D, const int32_t* __restrict__ tokens,
+                                                                    const T* __restrict__ dx0, float* __restrict__ g_tok,
+                                                                    const int* __restrict__ first,
+                                                                    const int* __restrict__ count) {
+  __shared__ unsigned map[EMB_WIN / 32];
+  const int t = blockIdx.x;
+  const int v = tokens[t];
+  if (first[v] != t) return;  // uniform over the workgroup: some earlier position owns this row
+  const int n = count[v];
+  float* g = g_tok + (size_t)v * D;
+  for (int d0 = 0; d0 < D; d0 += 256 * EMB_ACC) {
+    float acc[EMB_ACC];
+#pragma unroll
+    for (int k = 0; k < EMB_ACC; k++) acc[k] = 0.f;
+    int found = 0;
+    for (int base = t; found < n && base < Tn; base += EMB_WIN) {  // uniform; the n positions all lie at or after t
+      if (threadIdx.x < EMB_WIN / 32) map[threadIdx.x] = 0u;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < EMB_WIN / 256; j++) {
+        const int i = j * 256 + threadIdx.x;
+        if (base + i < Tn && tokens[base + i] == v) atomicOr(&map[i >> 5], 1u << (i & 31));
+      }
+      __syncthreads();
+      for (int w = 0; w < EMB_WIN / 32; w++) {
+        unsigned bits = map[w];
+        while (bits) {
+          const int pos = base + w * 32 + __ffs(bits) - 1;
+          bits &= bits - 1;
+          found++;
+          const T* dx = dx0 + (size_t)pos * D + d0;
+#pragma unroll
+          for (int k = 0; k < EMB_ACC; k++) {
+            const int d = threadIdx.x + 256 * k;
+            if (d0 + d < D) acc[k] += to_f(dx[d]);
+          }
+        }
+      }
+      __syncthreads();  // everyone has read the map before the next window clears it
+    }
+#pragma unroll
+    for (int k = 0; k < EMB_ACC; k++) {
+      const int d = d0 + threadIdx.x + 256 * k;
+      if (d < D) g[d] += acc[k];
+    }
+  }
+}
+
+size_t embed_index_ws_bytes(int V) { return (size_t)2 * (size_t)V * sizeof(int); }
+
+int embed_bwd(int dtype, int B, int S, int D, int V, const int32_t* tokens, const void* dx0, float* g_tok, float* g_pos,
+              bool accumulate_pos, void* index_ws, hipStream_t s) {
   if (B * S == 0) return FAX_OK;
   Timed t_("embed_bwd", WORK_BYTE, 2.0 * B * S * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * B * S * D + 4.0 * S * D, s);
-  if (dtype == FAX_F32) {
-    hipLaunchKernelGGL((embed_bwd_tok_kernel<float>), dim3(B * S), dim3(256), 0, s, D, tokens, (const float*)dx0, g_tok);
+  const int T = B * S;
+  if (index_ws) {  // ordered reduction
+    int* first = (int*)index_ws;
+    int* count = first + V;
+    hipLaunchKernelGGL(embed_index_init_kernel, dim3((V + 255) / 256), dim3(256), 0, s, V, first, count);
+    hipLaunchKernelGGL(embed_index_kernel, dim3((T + 255) / 256), dim3(256), 0, s, T, tokens, first, count);
+    if (dtype == FAX_F32)
+      hipLaunchKernelGGL((embed_bwd_tok_ordered_kernel<float>), dim3(T), dim3(256), 0, s, T, D, tokens, (const float*)dx0,
+                         g_tok, first, count);
+    else
+      hipLaunchKernelGGL((embed_bwd_tok_ordered_kernel<bf16_t>), dim3(T), dim3(256), 0, s, T, D, tokens, (const bf16_t*)dx0,
+                         g_tok, first, count);
+  } else if (dtype == FAX_F32) {
+    hipLaunchKernelGGL((embed_bwd_tok_kernel<float>), dim3(T), dim3(256), 0, s, D, tokens, (const float*)dx0, g_tok);
+  } else {
+    hipLaunchKernelGGL((embed_bwd_tok_kernel<bf16_t>), dim3(T), dim3(256), 0, s, D, tokens, (const bf16_t*)dx0, g_tok);
+  }
+  if (dtype == FAX_F32)
     hipLaunchKernelGGL((embed_bwd_pos_kernel<float>), dim3(S), dim3(256), 0, s, B, S, D, (const float*)dx0, g_pos,
                        accumulate_pos ? 1 : 0);
-  } else {
-    hipLaunchKernelGGL((embed_bwd_tok_kernel<bf16_t>), dim3(B * S), dim3(256), 0, s, D, tokens, (const bf16_t*)dx0, g_tok);
+  else
     hipLaunchKernelGGL((embed_bwd_pos_kernel<bf16_t>), dim3(S), dim3(256), 0, s, B, S, D, (const bf16_t*)dx0, g_pos,
                        accumulate_pos ? 1 : 0);
-  }
   FAX_LAUNCH_CHECK("embed_bwd");
   return FAX_OK;
 }

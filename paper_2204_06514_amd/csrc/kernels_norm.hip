@@ -1,9 +1,11 @@
 // LayerNorm forward/backward and column sums: HBM-bound kernels.
 //
 // Forward reads each row once (16-byte loads, row cached in registers), writes it once.
-// Backward: a row kernel reads dh and x once and writes dx once; the per-column sums for
-// dgamma/dbeta come from a second, column-parallel pass over dh and x (strips of rows summed
-// in registers, then folded in a fixed order), so no result depends on scheduling order.
+// Backward is one pass as well: a workgroup walks over row blocks, reads dh and x once, writes dx
+// once and keeps running per-column sums of dh * xhat and dh in registers; each workgroup leaves
+// one partial row of dgamma and of dbeta, and a second small kernel folds the partial rows in a
+// fixed order, so no result depends on scheduling order.  (Row lengths the vector kernels do not
+// cover fall back to a row kernel for dx plus a column-parallel pass for the two sums.)
 #include "fax_internal.h"
 
 namespace fax {

@@ -94,3 +94,43 @@ def run_block(sh, p, x, dy, gelu=None, partial=False, accumulate=False, grads_in
         out["p_attn"] = to_np(pa).reshape(x.shape)
         out["p_mlp"] = to_np(pm).reshape(x.shape)
     return out
+
+
+# ---- the first AdamW step, end to end ------------------------------------------------------------------
+# At step 1 from zero moments the update is lr g / (|g| + eps): every element moves by about lr in
+# the direction of -g, whatever |g| is.  Comparing updated parameters at a bar of a few lr would
+# therefore pass an update that does nothing (error lr) or goes the wrong way (2 lr).  What is
+# compared instead: the moments (linear and quadratic in g, so the gradient bar carries over), the
+# displacement master - p0 element by element against the oracle's (an element either agrees to
+# rounding or, where the gradient is within the kernels' noise of zero, has the other sign: a
+# small fraction), and that the displacement is there at all.
+def adamw_step_report(got_master, got_m, got_v, p0, g_ref, hp, keep=None, dtype="bf16", step=1):
+    """Failures (name -> value) of one tensor's first update.  All arguments float64 numpy;
+    `keep`: optional boolean mask of the elements that count (the key third of bqkv does not:
+    its gradient is analytically zero, so its first step is rounding noise times 1/eps)."""
+    from oracle import transformer as orc
+    ref_p, ref_m, ref_v = orc.adamw(p0, 0.0, 0.0, g_ref, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"], step)
+    sel = (lambda a: a[keep]) if keep is not None else (lambda a: a.reshape(-1))
+    gm, gv, gp, p0s = sel(got_m), sel(got_v), sel(got_master), sel(p0)
+    rm, rv, rp = sel(ref_m), sel(ref_v), sel(ref_p)
+    bad = {}
+    if dtype == "f32":
+        if rel_max(gm, rm) > 1e-5: bad["m"] = rel_max(gm, rm)
+        if rel_max(gv, rv) > 2e-5: bad["v"] = rel_max(gv, rv)
+        if np.abs(gp - rp).max() > 2.5e-3 * hp["lr"]: bad["p"] = np.abs(gp - rp).max()
+    else:
+        if rel_fro(gm, rm) > 2e-2: bad["m"] = rel_fro(gm, rm)
+        if rel_fro(gv, rv) > 4e-2: bad["v"] = rel_fro(gv, rv)
+        off = np.abs((gp - p0s) - (rp - p0s)) > 0.1 * hp["lr"]
+        if off.mean() > 0.01: bad["displaced_elsewhere"] = off.mean()
+    moved = np.abs(gp - p0s).max() if gp.size else 0.0
+    want = np.abs(rp - p0s).max() if rp.size else 0.0
+    if want > 0 and moved < 0.5 * want: bad["not_moved"] = moved
+    return bad
+
+
+def bqkv_keep(Hd):
+    """Mask of bqkv's query and value thirds."""
+    k = np.ones(3 * Hd, dtype=bool)
+    k[Hd:2 * Hd] = False
+    return k

@@ -48,6 +48,50 @@ def test_cfg1_fp32_block(gelu, generic):
     _check_block(sh, out, p, x, dy, gelu)
 
 
+@pytest.mark.parametrize("generic", [False, True])
+def test_cfg1_fp32_block_then_adamw_step(generic):
+    """The tiny configuration as it is defined: forward, backward, then one AdamW step (lr 1e-3,
+    betas 0.9 / 0.999, eps 1e-8, wd 0.01) on the block's own gradients; updated parameters and both
+    moments against the oracle's update of the oracle's gradients."""
+    import torch
+    import paper_2204_06514_amd as fax
+    from workloads.configs import ADAMW_DEFAULT
+    from helpers import dims_of, to_dev, to_np, DEV, adamw_step_report, bqkv_keep
+    sh = get_config("cfg1")
+    p, x, dy = make_block_inputs(sh, seed=0, generic=generic)
+    dims = dims_of(sh)
+    pd = {k: to_dev(p[k], "f32") for k in PARAM_NAMES}
+    xd, dyd = to_dev(x, "f32"), to_dev(dy, "f32")
+    saved = torch.empty(fax.fax_block_saved_layout(dims).total, dtype=torch.uint8, device=DEV)
+    wsb = fax.fax_block_workspace_bytes(dims)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
+    fax.fax_block_fwd(dims, pd, xd, y, saved, None, None, ws, wsb)
+    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, ws, wsb)
+    m = {k: torch.zeros_like(t) for k, t in pd.items()}
+    v = {k: torch.zeros_like(t) for k, t in pd.items()}
+    fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, m, v, gd)), None, fax.FaxAdamW(**ADAMW_DEFAULT), 1)
+    torch.cuda.synchronize()
+    _, c = orc.block_fwd(x, p, sh.H, sh.dh, "tanh", sh.ln_eps)
+    _, g, _ = orc.block_bwd(dy, c, p)
+    a = ADAMW_DEFAULT
+    bad = {}
+    for k in PARAM_NAMES:
+        keep = bqkv_keep(sh.Hd) if k == "bqkv" else None
+        r = adamw_step_report(to_np(pd[k]), to_np(m[k]), to_np(v[k]), p[k], g[k], a, keep=keep, dtype="f32")
+        ref, _, _ = orc.adamw(p[k], 0.0, 0.0, g[k], a["lr"], a["beta1"], a["beta2"], a["eps"], a["wd"], 1)
+        got = to_np(pd[k])
+        if keep is not None:
+            ref, got = ref[keep], got[keep]
+        e = rel_max(got, ref)
+        if e > 1e-5:
+            r["updated_parameters"] = e
+        if r:
+            bad[k] = r
+    assert not bad, bad
+
+
 def test_fp32_ragged_shapes_and_partial_sums():
     sh = BlockShape(B=3, S=37, D=72, H=3, dh=20, F=100, dtype="f32", sigma_w=0.05)
     p, x, dy = make_block_inputs(sh, seed=4, generic=True)

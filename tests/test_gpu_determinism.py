@@ -1,0 +1,115 @@
+"""Two runs on the same inputs return the same bits: the block's forward and backward pass as they
+are (one writer per output element, fixed-order reductions), and the whole training step with
+FAX_FLAG_DETERMINISTIC, which replaces the one kernel that uses floating-point atomics (the
+scatter-add of the token-embedding gradient) by an ordered reduction.  The ordered reduction is
+also compared with the oracle where token ids repeat often, repeat across several scan windows,
+and where a row is wider than one pass of the kernel covers."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2204_06514_amd as fax
+from oracle import transformer as orc
+from workloads import BlockShape, ModelShape, get_config, make_block_inputs, make_model_inputs, PARAM_NAMES
+from helpers import DEV, to_dev, to_np, err, tol, dims_of, view_bytes
+from test_gpu_train import run_train_step, _walk
+
+pytestmark = pytest.mark.gpu
+
+
+def _block_twice(sh, seed):
+    p, x, dy = make_block_inputs(sh, seed=seed, generic=True)
+    dims = dims_of(sh, fax.FAX_FLAG_TP_PARTIAL)
+    pd = {k: to_dev(p[k], sh.dtype) for k in PARAM_NAMES}
+    xd, dyd = to_dev(x, sh.dtype), to_dev(dy, sh.dtype)
+    lay = fax.fax_block_saved_layout(dims)
+    wsb = fax.fax_block_workspace_bytes(dims)
+    runs = []
+    for _ in range(2):
+        saved = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
+        ws = torch.zeros(wsb, dtype=torch.uint8, device=DEV)
+        y, pa, pm, dx = (torch.empty_like(xd) for _ in range(4))
+        gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
+        fax.fax_block_fwd(dims, pd, xd, y, saved, pa, pm, ws, wsb)
+        fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, ws, wsb)
+        torch.cuda.synchronize()
+        bl = fax.fax_block_bwd_layout(dims)
+        runs.append({"y": y, "p_attn": pa, "p_mlp": pm, "dx": dx, "saved": saved, "bwd": ws[:bl.dh1 + sh.T * sh.D * y.element_size()],
+                     **{"d" + k: t for k, t in gd.items()}})
+    return runs
+
+
+@pytest.mark.parametrize("sh", [get_config("cfg1"),
+                                BlockShape(B=2, S=256, D=256, H=4, dh=64, F=1024, dtype="bf16", sigma_w=0.02),
+                                BlockShape(B=2, S=1024, D=256, H=2, dh=128, F=512, dtype="bf16", sigma_w=0.02)],
+                         ids=lambda s: "%s_D%d_S%d" % (s.dtype, s.D, s.S))
+def test_block_forward_and_backward_are_bit_reproducible(sh):
+    a, b = _block_twice(sh, seed=7)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+
+
+CASES = [
+    # many repeated ids inside one scan window
+    ModelShape(BlockShape(B=2, S=128, D=128, H=2, dh=64, F=256, dtype="bf16", sigma_w=0.05, L=2), V=96, S_max=128),
+    # fp32, ragged width
+    ModelShape(BlockShape(B=2, S=24, D=36, H=2, dh=16, F=64, dtype="f32", sigma_w=0.1, L=1), V=17, S_max=32),
+    # 2560 positions (three scan windows) over 48 ids
+    ModelShape(BlockShape(B=2, S=1280, D=128, H=2, dh=64, F=256, dtype="bf16", sigma_w=0.05, L=1), V=48, S_max=1280),
+    # rows of 2176 columns: two passes of 2048 columns per workgroup
+    ModelShape(BlockShape(B=2, S=128, D=2176, H=17, dh=128, F=256, dtype="bf16", sigma_w=0.02, L=1), V=300, S_max=128),
+]
+
+
+@pytest.mark.parametrize("ms", CASES, ids=lambda m: "%s_D%d_V%d_T%d" % (m.blk.dtype, m.blk.D, m.V, m.blk.T))
+def test_ordered_embedding_gradient_matches_the_oracle_and_repeats_bit_for_bit(ms):
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=11, generic=True)
+    loss_ref, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    runs = [run_train_step(ms, p, tok, lab, update=True, flags=fax.FAX_FLAG_DETERMINISTIC) for _ in range(2)]
+    (loss_a, par_a, mas_a, m_a, v_a, g_a), (loss_b, par_b, mas_b, m_b, v_b, g_b) = runs
+    t = tol(sh.dtype)
+    for name, get in _walk(g_a):
+        assert err(to_np(get(g_a)), get(g_ref), sh.dtype) <= t, name
+        assert torch.equal(get(g_a), get(g_b)), name
+        assert torch.equal(get(mas_a), get(mas_b)) and torch.equal(get(m_a), get(m_b)) and torch.equal(get(v_a), get(v_b)), name
+    assert loss_a == loss_b
+
+
+def test_one_token_id_everywhere():
+    """Every position holds the same id: one workgroup owns the row and adds all 2560 positions."""
+    ms = CASES[2]
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=12)
+    tok = np.full_like(tok, 5)
+    _, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    _, _, _, _, _, g = run_train_step(ms, p, tok, lab, update=False, flags=fax.FAX_FLAG_DETERMINISTIC)
+    assert err(to_np(g["tok_emb"]), g_ref["tok_emb"], sh.dtype) <= tol(sh.dtype)
+    _, _, _, _, _, g2 = run_train_step(ms, p, tok, lab, update=False)   # the atomic path on the same input
+    assert err(to_np(g2["tok_emb"]), g_ref["tok_emb"], sh.dtype) <= tol(sh.dtype)
+
+
+def test_accumulating_micro_batches_with_the_ordered_reduction():
+    ms = CASES[0]
+    sh = ms.blk
+    p, tok, lab = make_model_inputs(ms, seed=13, generic=True)
+    _, g_ref, _ = orc.model_loss_and_grads(p, tok, lab, sh.H, sh.dh, sh.gelu, sh.ln_eps)
+    from test_gpu_train import _dev_params, _like
+    from workloads.configs import ADAMW_DEFAULT
+    half = ms.scaled(B=1)
+    outs = []
+    for _ in range(2):
+        params = _dev_params(p, sh.dtype)
+        master = _like(params, src=params); m = _like(params, 0.0); v = _like(params, 0.0); grads = _like(params, 7.0)
+        loss = torch.zeros(4, device=DEV)
+        for i, flags in enumerate((fax.FAX_FLAG_SKIP_UPDATE, fax.FAX_FLAG_ACCUMULATE | fax.FAX_FLAG_SKIP_UPDATE)):
+            md = fax.FaxModelDims(dims_of(half.blk), sh.L, ms.V, ms.S_max, flags | fax.FAX_FLAG_DETERMINISTIC, 2)
+            wsb = fax.fax_train_workspace_bytes(md)
+            ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+            fax.fax_train_step(md, params, master, m, v, grads, torch.from_numpy(tok[i:i + 1].copy()).to(DEV),
+                               torch.from_numpy(lab[i:i + 1].copy()).to(DEV), fax.FaxAdamW(**ADAMW_DEFAULT), 1, loss, ws, wsb)
+        torch.cuda.synchronize()
+        outs.append(grads)
+    for name, get in _walk(outs[0]):
+        assert err(to_np(get(outs[0])), get(g_ref), sh.dtype) <= tol(sh.dtype), name
+        assert torch.equal(get(outs[0]), get(outs[1])), name
