@@ -5,13 +5,24 @@
 namespace fax {
 
 // ---------------------------------------------------------------------------------------------
-// Cross-entropy.  One 1024-thread block per row; the row is read from HBM once (cached in
-// registers as raw 16-byte vectors when it fits), reduced to max and sum-exp, and the gradient
-// grad_scale (softmax - onehot)/N is written over it (or anywhere else; nowhere when dlogits is NULL:
-// loss only).
+// Cross-entropy.  One workgroup per row.  The row is read from HBM once and kept in registers as
+// the raw 16-byte vectors it arrived in; the gradient grad_scale (softmax - onehot)/N is written
+// over it (or anywhere else; nowhere when dlogits is NULL: loss only), so the logits cross HBM
+// once in each direction.
+//
+// What bounds it besides HBM is the vector unit (one exponential per logit and pass, quarter
+// rate), so the arithmetic is kept short: the exponentials are single v_exp_f32 instructions on
+// (z - maximum) log2(e); each thread first reduces its
+// own elements to a (maximum, sum of 2^(t - maximum)) pair and the pairs are then combined across
+// the workgroup in one step (one barrier instead of one per reduction); the one element that
+// carries the label is patched by the thread that holds it instead of every element being
+// compared with the label.  The workgroup size is chosen on the host so that the row divides
+// evenly over the threads (51200 bf16 logits: 640 threads x 10 vectors).
 // ---------------------------------------------------------------------------------------------
-static constexpr int CE_THREADS = 1024;
-static constexpr int CE_MAXV = 8;
+static constexpr int CE_MAX_THREADS = 1024;
+static constexpr int CE_MAX_NV = 16;
+static constexpr float CE_LOG2E = 1.4426950408889634f;
+static constexpr float CE_LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
   v = is_max ? wave_max(v) : wave_sum(v);
@@ -24,73 +35,111 @@ __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) 
   return r;
 }
 
-template <typename T, bool CACHED>
-__global__ __launch_bounds__(CE_THREADS) void ce_kernel(int N, int V, const T* __restrict__ logits,
-                                                        const int32_t* __restrict__ labels, T* __restrict__ dlogits,
-                                                        float* __restrict__ row_loss, float grad_scale) {
+// NV: 16-byte vectors per thread (V <= blockDim.x * NV * elements per vector, V a multiple of the latter).
+template <typename T, int NV>
+__global__ __launch_bounds__(CE_MAX_THREADS) void ce_cached_kernel(int N, int V, const T* __restrict__ logits,
+                                                                   const int32_t* __restrict__ labels,
+                                                                   T* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                                   float grad_scale) {
   using Vv = Vec16<T>;
-  __shared__ float red[CE_THREADS / 64];
+  __shared__ float red_m[CE_MAX_THREADS / 64], red_s[CE_MAX_THREADS / 64];
+  const int row = blockIdx.x;
+  const T* z = logits + (size_t)row * V;
+  const int nvec = V / Vv::N;
+  const int nt = blockDim.x;
+  const int label = labels[row];
+  // read before the barrier below, i.e. before any thread of the workgroup overwrites the row (dz may alias z)
+  const float z_label = threadIdx.x == 0 ? to_f(z[label]) : 0.f;
+  Vv zv[NV];
+#pragma unroll
+  for (int i = 0; i < NV; i++) {
+    const int c = threadIdx.x + i * nt;
+    if (c < nvec) zv[i].load(z + (size_t)c * Vv::N);
+  }
+  // this thread's maximum, then its sum of e^(z - maximum) (differences first, then the scale to base 2)
+  float mt = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; i++) {
+    if (threadIdx.x + i * nt < nvec) {
+#pragma unroll
+      for (int e = 0; e < Vv::N; e++) mt = fmaxf(mt, zv[i].get(e));
+    }
+  }
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; i++) {
+    if (threadIdx.x + i * nt < nvec) {
+#pragma unroll
+      for (int e = 0; e < Vv::N; e++) se += __builtin_amdgcn_exp2f((zv[i].get(e) - mt) * CE_LOG2E);
+    }
+  }
+  // combine the (maximum, sum) pairs: within the wave, then across waves through LDS.  A thread
+  // without elements has maximum -inf and sum 0 and drops out.
+  const float mw = wave_max(mt);
+  const float sw = wave_sum(mt == -INFINITY ? 0.f : se * __builtin_amdgcn_exp2f((mt - mw) * CE_LOG2E));
+  const int wave = threadIdx.x >> 6, nw = nt >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    red_m[wave] = mw;
+    red_s[wave] = sw;
+  }
+  __syncthreads();
+  float M = red_m[0];
+  for (int i = 1; i < nw; i++) M = fmaxf(M, red_m[i]);
+  float S = 0.f;
+  for (int i = 0; i < nw; i++)  // fixed order
+    S += red_m[i] == -INFINITY ? 0.f : red_s[i] * __builtin_amdgcn_exp2f((red_m[i] - M) * CE_LOG2E);
+  if (threadIdx.x == 0) row_loss[row] = (M + __builtin_amdgcn_logf(S) * CE_LN2) - z_label;  // v_log_f32 is log2
+  if (!dlogits) return;
+  const float invN = grad_scale / (float)N;
+  const float inv = invN / S;
+  T* dz = dlogits + (size_t)row * V;
+#pragma unroll
+  for (int i = 0; i < NV; i++) {
+    const int c = threadIdx.x + i * nt;
+    if (c < nvec) {
+      float g[Vv::N];
+#pragma unroll
+      for (int e = 0; e < Vv::N; e++) g[e] = __builtin_amdgcn_exp2f((zv[i].get(e) - M) * CE_LOG2E) * inv;
+      const int k = label - c * Vv::N;
+      if (k >= 0 && k < Vv::N) {  // rare: the vector that holds the label's column
+#pragma unroll
+        for (int e = 0; e < Vv::N; e++)
+          if (e == k) g[e] -= invN;
+      }
+      Vv o;
+#pragma unroll
+      for (int e = 0; e < Vv::N; e++) o.set(e, g[e]);
+      o.store(dz + (size_t)c * Vv::N);
+    }
+  }
+}
+
+// Any V: three passes over the row in memory (the re-reads hit cache).
+template <typename T>
+__global__ __launch_bounds__(CE_MAX_THREADS) void ce_generic_kernel(int N, int V, const T* __restrict__ logits,
+                                                                    const int32_t* __restrict__ labels,
+                                                                    T* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                                    float grad_scale) {
+  __shared__ float red[CE_MAX_THREADS / 64];
   const int row = blockIdx.x;
   const T* z = logits + (size_t)row * V;
   T* dz = dlogits + (size_t)row * V;
-  const int nvec = V / Vv::N;  // CACHED requires V % Vv::N == 0
   const int label = labels[row];
   const float invN = grad_scale / (float)N;
-  Vv zv[CE_MAXV];
   float mx = -INFINITY;
-  if (CACHED) {
-#pragma unroll
-    for (int i = 0; i < CE_MAXV; i++) {
-      const int c = threadIdx.x + i * CE_THREADS;
-      if (c < nvec) {
-        zv[i].load(z + c * Vv::N);
-#pragma unroll
-        for (int e = 0; e < Vv::N; e++) mx = fmaxf(mx, zv[i].get(e));
-      }
-    }
-  } else {
-    for (int c = threadIdx.x; c < V; c += CE_THREADS) mx = fmaxf(mx, to_f(z[c]));
-  }
+  for (int c = threadIdx.x; c < V; c += blockDim.x) mx = fmaxf(mx, to_f(z[c]));
   mx = block_reduce(mx, red, true);
   float se = 0.f;
-  if (CACHED) {
-#pragma unroll
-    for (int i = 0; i < CE_MAXV; i++) {
-      const int c = threadIdx.x + i * CE_THREADS;
-      if (c < nvec) {
-#pragma unroll
-        for (int e = 0; e < Vv::N; e++) se += expf(zv[i].get(e) - mx);
-      }
-    }
-  } else {
-    for (int c = threadIdx.x; c < V; c += CE_THREADS) se += expf(to_f(z[c]) - mx);
-  }
+  for (int c = threadIdx.x; c < V; c += blockDim.x) se += expf(to_f(z[c]) - mx);
   se = block_reduce(se, red, false);
   const float inv = invN / se;
   if (threadIdx.x == 0) row_loss[row] = (mx + logf(se)) - to_f(z[label]);
   if (!dlogits) return;
   __syncthreads();  // z[label] is read before anyone overwrites it (dz may alias z)
-  if (CACHED) {
-#pragma unroll
-    for (int i = 0; i < CE_MAXV; i++) {
-      const int c = threadIdx.x + i * CE_THREADS;
-      if (c < nvec) {
-        Vv o;
-#pragma unroll
-        for (int e = 0; e < Vv::N; e++) {
-          float g = expf(zv[i].get(e) - mx) * inv;
-          if (c * Vv::N + e == label) g -= invN;
-          o.set(e, g);
-        }
-        o.store(dz + c * Vv::N);
-      }
-    }
-  } else {
-    for (int c = threadIdx.x; c < V; c += CE_THREADS) {
-      float g = expf(to_f(z[c]) - mx) * inv;
-      if (c == label) g -= invN;
-      dz[c] = from_f<T>(g);
-    }
+  for (int c = threadIdx.x; c < V; c += blockDim.x) {
+    float g = expf(to_f(z[c]) - mx) * inv;
+    if (c == label) g -= invN;
+    dz[c] = from_f<T>(g);
   }
 }
 
@@ -103,16 +152,43 @@ __global__ __launch_bounds__(1024) void mean_kernel(int N, const float* __restri
   if (threadIdx.x == 0) *out = s / (float)N;
 }
 
+// Threads per row and vectors per thread for a row of `nvec` 16-byte vectors: the pair with the
+// fewest idle vector slots among workgroups of 4 to 16 waves; of equals, the larger workgroup.
+static bool ce_shape(int nvec, int* threads, int* nv) {
+  long best = -1;
+  for (int nt = CE_MAX_THREADS; nt >= 256; nt -= 64) {
+    const int v = (nvec + nt - 1) / nt;
+    if (v > CE_MAX_NV) continue;
+    const int vt = v <= 2 ? 2 : v <= 4 ? 4 : v <= 6 ? 6 : v <= 8 ? 8 : v <= 10 ? 10 : v <= 12 ? 12 : 16;  // instantiated sizes
+    const long waste = (long)nt * vt - nvec;
+    if (best < 0 || waste < best) {
+      best = waste;
+      *threads = nt;
+      *nv = vt;
+    }
+  }
+  return best >= 0;
+}
+
 template <typename T>
 static int ce_t(int N, int V, const T* logits, const int32_t* labels, T* dlogits, float* row_loss, float* loss_out,
                 float grad_scale, hipStream_t s) {
   constexpr int VN = Vec16<T>::N;
-  if (V % VN == 0 && V / VN <= CE_THREADS * CE_MAXV)
-    hipLaunchKernelGGL((ce_kernel<T, true>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss,
+  int nt = 0, nv = 0;
+  if (V % VN == 0 && ce_shape(V / VN, &nt, &nv)) {
+#define FAX_CE(NVT)                                                                                                  \
+  case NVT:                                                                                                          \
+    hipLaunchKernelGGL((ce_cached_kernel<T, NVT>), dim3(N), dim3(nt), 0, s, N, V, logits, labels, dlogits, row_loss, \
+                       grad_scale);                                                                                  \
+    break
+    switch (nv) {
+      FAX_CE(2); FAX_CE(4); FAX_CE(6); FAX_CE(8); FAX_CE(10); FAX_CE(12); FAX_CE(16);
+    }
+#undef FAX_CE
+  } else {
+    hipLaunchKernelGGL((ce_generic_kernel<T>), dim3(N), dim3(CE_MAX_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss,
                        grad_scale);
-  else
-    hipLaunchKernelGGL((ce_kernel<T, false>), dim3(N), dim3(CE_THREADS), 0, s, N, V, logits, labels, dlogits, row_loss,
-                       grad_scale);
+  }
   FAX_LAUNCH_CHECK("cross_entropy");
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, s, N, row_loss, loss_out);
   FAX_LAUNCH_CHECK("cross_entropy_mean");
