@@ -326,6 +326,25 @@ int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t
                       void* dlogits, float* row_loss, float* loss_out, void* stream);
 
 /*
+ * fax_cross_entropy for callers that cannot allocate device memory or may not call an allocator
+ * where they stand: code under HIP graph capture, tight serving or evaluation loops, harnesses
+ * that forbid hipMalloc.  Same kernels and same results as fax_cross_entropy; the per-row losses
+ * (the one scratch buffer of that call) live in a device array built into the library instead of
+ * a buffer of the caller's, so the call needs nothing but its inputs and outputs.  It allocates
+ * and frees nothing and calls no allocating routine.
+ *   Limit: N <= fax_cross_entropy_static_max_rows() = 262144 rows (1 MiB of scratch per GPU, held
+ *   from the first use on that GPU until the process ends); more rows: FAX_ERR_WORKSPACE, nothing
+ *   enqueued.
+ *   The device that owns `stream` must be the current device.  All calls on one GPU share the one
+ *   array: calls that overlap in time on the same GPU (different streams, or different threads)
+ *   race on it; calls on one stream, or ordered by events, do not.  Nothing has to be cleared
+ *   between calls: every entry a call reads it has written before.
+ */
+int fax_cross_entropy_static(int dtype, int N, int V, const void* logits, const int32_t* labels,
+                             void* dlogits, float* loss_out, void* stream);
+int fax_cross_entropy_static_max_rows(void);
+
+/*
  * Per-kernel timing with HIP events on the caller's stream: the split of a step into its
  * phases that Fig. 4 reports, at kernel granularity.  Off by default (no events recorded).
  * fax_timing_enable(1) clears earlier records and starts recording a start/stop event pair

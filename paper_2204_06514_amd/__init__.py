@@ -119,6 +119,8 @@ def _load():
         "fax_attention_fwd": (i32, [i32] * 5 + [vp, vp, vp, i32, vp]),
         "fax_attention_bwd": (i32, [i32] * 5 + [vp, vp, vp, vp, vp, vp, i32, vp]),
         "fax_cross_entropy": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "fax_cross_entropy_static": (i32, [i32, i32, i32, vp, vp, vp, vp, vp]),
+        "fax_cross_entropy_static_max_rows": (i32, []),
         "fax_analyze": (i32, [P(FaxModelDims), P(FaxMesh), P(FaxAnalysis)]),
         "fax_timing_enable": (i32, [i32]),
         "fax_timing_report": (i32, [P(FaxKernelTime), i32, P(i32)]),
@@ -321,3 +323,11 @@ def fax_cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, 
     _check(_lib.fax_cross_entropy(dtype, N, V, _ptr(logits), _ptr(labels), _ptr(dlogits), _ptr(row_loss),
                                   _ptr(loss_out), _stream(stream)))
 
+
+def fax_cross_entropy_static(dtype, N, V, logits, labels, dlogits, loss_out, stream=None):
+    _check(_lib.fax_cross_entropy_static(dtype, N, V, _ptr(logits), _ptr(labels), _ptr(dlogits), _ptr(loss_out),
+                                         _stream(stream)))
+
+
+def fax_cross_entropy_static_max_rows():
+    return _lib.fax_cross_entropy_static_max_rows()

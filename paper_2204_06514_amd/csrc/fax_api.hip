@@ -828,4 +828,15 @@ int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t
   return cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, 1.0f, (hipStream_t)stream);
 }
 
+int fax_cross_entropy_static(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
+                             float* loss_out, void* stream) {
+  if (dtype != FAX_F32 && dtype != FAX_BF16) { set_error("bad dtype %d", dtype); return FAX_ERR_INVALID_ARG; }
+  if (N <= 0 || V <= 0) { set_error("bad cross-entropy size N=%d V=%d", N, V); return FAX_ERR_INVALID_ARG; }
+  FAX_TRY(check_ptr(logits, "logits")); FAX_TRY(check_ptr(labels, "labels")); FAX_TRY(check_ptr(dlogits, "dlogits"));
+  FAX_TRY(check_ptr(loss_out, "loss_out"));
+  return cross_entropy_static(dtype, N, V, logits, labels, dlogits, loss_out, (hipStream_t)stream);
+}
+
+int fax_cross_entropy_static_max_rows(void) { return CE_STATIC_MAX_ROWS; }
+
 }  // extern "C"

@@ -111,6 +111,10 @@ int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx,
 // dlogits = grad_scale (softmax - onehot) / N, may alias logits, NULL for the loss alone
 int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
                   float* row_loss, float* loss_out, float grad_scale, hipStream_t s);
+// Per-row losses in a file-scope device array of the library (CE_STATIC_MAX_ROWS floats, 1 MiB per GPU).
+constexpr int CE_STATIC_MAX_ROWS = 1 << 18;
+int cross_entropy_static(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
+                         float* loss_out, hipStream_t s);
 int embed_fwd(int dtype, int B, int S, int D, const int32_t* tokens, const void* tok_emb, const void* pos_emb,
               void* x0, hipStream_t s);
 // g_tok[tokens[b,s]] += dx0[b,s]; g_pos[s] (+)= sum_b dx0[b,s]; rows of g_pos beyond S untouched.

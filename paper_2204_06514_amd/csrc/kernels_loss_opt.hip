@@ -1,5 +1,7 @@
 // HBM-bound kernels around the blocks: softmax cross-entropy (forward + gradient in one pass
 // over the logits), embedding gather / scatter, and the AdamW update.
+#include <mutex>
+
 #include "fax_internal.h"
 
 namespace fax {
@@ -202,6 +204,48 @@ int cross_entropy(int dtype, int N, int V, const void* logits, const int32_t* la
   if (dtype == FAX_F32)
     return ce_t<float>(N, V, (const float*)logits, labels, (float*)dlogits, row_loss, loss_out, grad_scale, s);
   return ce_t<bf16_t>(N, V, (const bf16_t*)logits, labels, (bf16_t*)dlogits, row_loss, loss_out, grad_scale, s);
+}
+
+// The same with the per-row losses in a buffer that belongs to the library instead of the caller:
+// for callers that cannot allocate (code under graph capture, loops that must not call the
+// allocator).  `ce_scratch` is device memory of this code object, one copy per GPU, alive until
+// the process ends.  Its name is only a handle on the host: the device address is looked up once
+// per device, with that device current, and only that address is passed to kernels.
+static __device__ __align__(256) float ce_scratch[CE_STATIC_MAX_ROWS];
+static constexpr int MAX_DEVICES = 64;
+static float* g_ce_scratch_addr[MAX_DEVICES];  // per device; written once under the mutex
+static std::mutex g_ce_scratch_mu;
+
+int cross_entropy_static(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
+                         float* loss_out, hipStream_t s) {
+  if (N > CE_STATIC_MAX_ROWS) {
+    set_error("fax_cross_entropy_static: %d rows exceed the built-in scratch of %d rows; use fax_cross_entropy "
+              "with a row_loss buffer of your own", N, CE_STATIC_MAX_ROWS);
+    return FAX_ERR_WORKSPACE;
+  }
+  int dev = -1;
+  FAX_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) {
+    set_error("fax_cross_entropy_static: device ordinal %d not in [0, %d)", dev, MAX_DEVICES);
+    return FAX_ERR_UNSUPPORTED;
+  }
+  float* row_loss;
+  {
+    std::lock_guard<std::mutex> lk(g_ce_scratch_mu);
+    if (!g_ce_scratch_addr[dev]) {
+      void* addr = nullptr;
+      FAX_HIP(hipGetSymbolAddress(&addr, HIP_SYMBOL(ce_scratch)));
+      if (!addr) {
+        set_error("fax_cross_entropy_static: no device address for the scratch array on device %d", dev);
+        return FAX_ERR_HIP;
+      }
+      g_ce_scratch_addr[dev] = (float*)addr;
+    }
+    row_loss = g_ce_scratch_addr[dev];
+  }
+  // Every row < N of the scratch is written by the row kernel before the mean reads it, and no row
+  // >= N is read: nothing has to be cleared between calls.
+  return cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, 1.0f, s);
 }
 
 // ---------------------------------------------------------------------------------------------
