@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (the same C-ABI calls) in a HIP graph and time its replays")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured MFMA-only and copy-kernel ceilings")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain elementwise copy kernel (reads 256 MiB, writes 128 MiB): a known-size reference "
                          "for the HBM byte counters")
@@ -205,6 +206,21 @@ def main():
         for k in kernels:
             print(json.dumps(k), file=sys.stderr)
 
+    # Measured ceilings of this very GPU, after the timed regions: the matrix cores fed from registers
+    # only (operands zero / random: the chip holds different clocks for the two) and a plain copy.
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measure_ceilings(fax, torch, dev)
+        if roof["bound"] == "mfma":
+            roof["frac_of_measured_mfma_random"] = round(roof["achieved"] / ceilings["mfma_bf16_random_tflops"], 4)
+        else:
+            roof["frac_of_measured_copy"] = round(roof["achieved"] / ceilings["copy_gbs"], 4)
+        for k in kernels:
+            if "tflops" in k:
+                k["of_measured_mfma"] = round(k["tflops"] / ceilings["mfma_bf16_random_tflops"], 3)
+            else:
+                k["of_measured_copy"] = round(k["gbs"] / ceilings["copy_gbs"], 3)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(args.config, cfg)
@@ -219,10 +235,41 @@ def main():
         "model_tflops": round(tflops, 2), "mfma_peak_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "model_tflops_unhalved_attention": round(flops_full / dt / 1e12, 2),
         "model_flop_per_step": flops,
-        "roofline": roof, "cpu_baseline": cpu, "phases": phases or None,
+        "mfma_frac_of_measured": (round(tflops / ceilings["mfma_bf16_random_tflops"], 4) if ceilings else None),
+        "roofline": roof, "ceilings": ceilings, "cpu_baseline": cpu, "phases": phases or None,
         "analysis": analysis if is_model else None, "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+def measure_ceilings(fax, torch, dev):
+    """MFMA-only and copy-only kernels of the library, timed with its HIP events: what this GPU
+    sustains when nothing but the matrix cores (256 workgroups of 4 waves, as the GEMM runs) or
+    nothing but HBM is in the way."""
+    sink = torch.zeros(4, device=dev)
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(3)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    iters = 40000          # 256 x 4 x 40000 x 16 MFMAs = 21.5 TFLOP: about 10 ms
+    for seed in (0, 1):    # untimed first launches
+        fax.fax_probe_mfma(cus, iters // 10, seed, sink)
+    fax.fax_probe_copy(src, dst, n)
+    torch.cuda.synchronize()
+    fax.fax_timing_enable(1)
+    for _ in range(3):
+        fax.fax_probe_mfma(cus, iters, 0, sink)
+        fax.fax_probe_mfma(cus, iters, 1, sink)
+        fax.fax_probe_copy(src, dst, n)
+    torch.cuda.synchronize()
+    rows = {r["name"]: r for r in fax.fax_timing_report(16)}
+    fax.fax_timing_enable(0)
+    rate = lambda r: r["work"] / (r["ms"] * 1e-3)
+    return {"mfma_bf16_zero_tflops": round(rate(rows["probe_mfma_zero"]) / 1e12, 1),
+            "mfma_bf16_random_tflops": round(rate(rows["probe_mfma_random"]) / 1e12, 1),
+            "copy_gbs": round(rate(rows["probe_copy"]) / 1e9, 1),
+            "how": "fax_probe_mfma: %d workgroups x 4 waves x %d x 16 back-to-back 32x32x16 bf16 MFMAs on register operands "
+                   "(zero / pseudo-random), fax_probe_copy: 1 GiB read + 1 GiB written; HIP events, 3 launches each" % (cus, iters)}
 
 
 def committed_traffic(config, kernel):
@@ -256,7 +303,17 @@ def cpu_baseline(name, cfg):
         orc.model_loss_and_grads(p, tok, lab, small.blk.H, small.blk.dh)
         dt = time.perf_counter() - t0
         toks = small.blk.T
-        sample = "oracle loss+gradients of the same model cut to B=1, S=512, L=2, V=8192 (float64), one run"
+        sample = ("oracle loss+gradients of the same model cut to B=1, S=512, L=2, V=8192 (float64), one run; the whole "
+                  "configuration would take more than ten minutes")
+    elif name == "cfg3":
+        # the whole configuration: about half a minute of float64 matrix products on 16 cores
+        p, x, dy = make_block_inputs(cfg, seed=0)
+        t0 = time.perf_counter()
+        _, c = orc.block_fwd(x, p, cfg.H, cfg.dh)
+        orc.block_bwd(dy, c, p)
+        dt = time.perf_counter() - t0
+        toks = cfg.T
+        sample = "the whole workload, no sampling: oracle block forward+backward at B=%d, S=%d (float64), one run" % (cfg.B, cfg.S)
     else:
         S = min(cfg.S, 2048 if cfg.D <= 4096 else 1024 if cfg.D <= 12288 else 512)
         small = cfg.scaled(B=1, S=S, L=1)
@@ -266,7 +323,8 @@ def cpu_baseline(name, cfg):
         orc.block_bwd(dy, c, p)
         dt = time.perf_counter() - t0
         toks = small.T
-        sample = "oracle block forward+backward on one batch row (B=1, S=%d) of the same block (float64), one run" % S
+        sample = ("oracle block forward+backward on one batch row (B=1, S=%d) of the same block (float64), one run; the "
+                  "whole configuration would take minutes" % S)
     return {"value": round(toks / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle", "sample": sample,
             "seconds": round(dt, 2)}
 

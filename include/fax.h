@@ -345,6 +345,19 @@ int fax_cross_entropy_static(int dtype, int N, int V, const void* logits, const 
 int fax_cross_entropy_static_max_rows(void);
 
 /*
+ * Measured ceilings, for benchmarks: what this GPU delivers to a kernel that does nothing but
+ * matrix-core instructions, and to one that does nothing but copy.  Timed like every other kernel
+ * through fax_timing_enable / fax_timing_report (rows "probe_mfma_zero", "probe_mfma_random",
+ * "probe_copy").
+ * fax_probe_mfma: `workgroups` x 4 waves each issue iters x 16 back-to-back 32x32x16 bf16 MFMAs on
+ *   register operands (seed 0: all zero; otherwise pseudo-random finite values): 2 * 32 * 32 * 16
+ *   flop each.  sink: one fp32 on the device (never written in practice).
+ * fax_probe_copy: dst[0, bytes) = src[0, bytes), bytes a multiple of 16; both on the device.
+ */
+int fax_probe_mfma(int workgroups, int iters, unsigned seed, float* sink, void* stream);
+int fax_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
  * Per-kernel timing with HIP events on the caller's stream: the split of a step into its
  * phases that Fig. 4 reports, at kernel granularity.  Off by default (no events recorded).
  * fax_timing_enable(1) clears earlier records and starts recording a start/stop event pair

@@ -121,6 +121,8 @@ def _load():
         "fax_cross_entropy": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "fax_cross_entropy_static": (i32, [i32, i32, i32, vp, vp, vp, vp, vp]),
         "fax_cross_entropy_static_max_rows": (i32, []),
+        "fax_probe_mfma": (i32, [i32, i32, C.c_uint, vp, vp]),
+        "fax_probe_copy": (i32, [vp, vp, sz, vp]),
         "fax_analyze": (i32, [P(FaxModelDims), P(FaxMesh), P(FaxAnalysis)]),
         "fax_timing_enable": (i32, [i32]),
         "fax_timing_report": (i32, [P(FaxKernelTime), i32, P(i32)]),
@@ -331,3 +333,11 @@ def fax_cross_entropy_static(dtype, N, V, logits, labels, dlogits, loss_out, str
 
 def fax_cross_entropy_static_max_rows():
     return _lib.fax_cross_entropy_static_max_rows()
+
+
+def fax_probe_mfma(workgroups, iters, seed, sink, stream=None):
+    _check(_lib.fax_probe_mfma(workgroups, iters, seed, _ptr(sink), _stream(stream)))
+
+
+def fax_probe_copy(src, dst, nbytes, stream=None):
+    _check(_lib.fax_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))

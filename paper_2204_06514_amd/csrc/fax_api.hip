@@ -828,6 +828,21 @@ int fax_cross_entropy(int dtype, int N, int V, const void* logits, const int32_t
   return cross_entropy(dtype, N, V, logits, labels, dlogits, row_loss, loss_out, 1.0f, (hipStream_t)stream);
 }
 
+int fax_probe_mfma(int workgroups, int iters, unsigned seed, float* sink, void* stream) {
+  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24)) {
+    set_error("fax_probe_mfma: workgroups=%d iters=%d out of range", workgroups, iters);
+    return FAX_ERR_INVALID_ARG;
+  }
+  FAX_TRY(check_ptr(sink, "sink"));
+  return probe_mfma(workgroups, iters, seed, sink, (hipStream_t)stream);
+}
+
+int fax_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (bytes == 0 || bytes % 16) { set_error("fax_probe_copy: bytes must be a positive multiple of 16"); return FAX_ERR_INVALID_ARG; }
+  FAX_TRY(check_ptr(src, "src")); FAX_TRY(check_ptr(dst, "dst"));
+  return probe_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 int fax_cross_entropy_static(int dtype, int N, int V, const void* logits, const int32_t* labels, void* dlogits,
                              float* loss_out, void* stream) {
   if (dtype != FAX_F32 && dtype != FAX_BF16) { set_error("bad dtype %d", dtype); return FAX_ERR_INVALID_ARG; }

@@ -154,6 +154,10 @@ int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size
           hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
 
+// ---- measured ceilings (probes.hip) ---------------------------------------------------------------
+int probe_mfma(int workgroups, int iters, unsigned seed, float* sink, hipStream_t s);
+int probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
 // ---- optional per-kernel timing (see fax_timing_enable) ------------------------------------
 enum { WORK_FLOP = 0, WORK_BYTE = 1 };
 bool timing_on();

@@ -100,15 +100,17 @@ constexpr bool em_gelu(int em) { return em_kind(em) == EK_GELU_TANH || em_kind(e
 
 // tanh-form GELU through the logistic function: (1 + tanh z) / 2 = 1 / (1 + exp(-2 z)), one
 // v_exp_f32 and one v_rcp_f32 per element, a few ulp in fp32 (the outputs are rounded to bf16).
-__device__ __forceinline__ float sigmoid2z(float u) {
-  const float z2 = 1.5957691216057308f * (u + 0.044715f * u * u * u);  // 2 sqrt(2/pi) (u + k u^3)
-  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z2));
-}
-// gelu(u) and gelu'(u) from the one logistic value
+// This runs in the GEMM's epilogue with the matrix cores idle, so the operation count matters:
+// 18 issue slots per element (the two quarter-rate instructions count four each), with u^2
+// shared between the argument and the derivative and every constant folded:
+//   -2 z log2(e) = u (A + B u^2),  A = -2 sqrt(2/pi) log2(e),  B = 0.044715 A
+//   gelu = u s,  gelu' = s + (gelu - gelu s) (C + D u^2),  C = 2 sqrt(2/pi),  D = 3 * 0.044715 C
 __device__ __forceinline__ void gelu_tanh_both(float u, float& g, float& dg) {
-  const float sg = sigmoid2z(u);
+  const float u2 = u * u;
+  const float e = __builtin_amdgcn_exp2f(u * fmaf(-0.10294324f, u2, -2.3022082f));
+  const float sg = __builtin_amdgcn_rcpf(1.f + e);
   g = u * sg;
-  dg = sg + (g - g * sg) * (1.5957691216057308f + 0.21406149f * u * u);  // 2 sqrt(2/pi) (1 + 3 k u^2)
+  dg = fmaf(fmaf(-g, sg, g), fmaf(0.21406445f, u2, 1.5957691216057308f), sg);
 }
 
 // Four consecutive columns n..n+3 of row m at once: 8-byte bf16 loads and stores.

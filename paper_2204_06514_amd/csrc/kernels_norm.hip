@@ -515,7 +515,7 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
   hipLaunchKernelGGL((ln_bwd_fused_kernel<T, TPR, NV>), dim3(grid(LN_THREADS / TPR)), dim3(LN_THREADS), 0, s, rows, D, \
                      dh, x, mu, rstd, gamma, dres, dx, partial)
     if (nvec <= 64 * 2) FAX_LN_BWD_FUSED(64, 2);
-    else if (nvec <= 64 * 4) FAX_LN_BWD_FUSED(64, 4);
+    else if (nvec <= 128 * 2) FAX_LN_BWD_FUSED(128, 2);  // D = 2048: twice the workgroups of (64, 4) at two thirds of its registers
     else if (nvec <= 256 * 2) FAX_LN_BWD_FUSED(256, 2);
     else if (nvec <= 256 * 3) FAX_LN_BWD_FUSED(256, 3);
     else if (nvec <= 256 * 4) FAX_LN_BWD_FUSED(256, 4);
