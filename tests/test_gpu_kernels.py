@@ -200,6 +200,28 @@ def test_cross_entropy(dtype, N, V):
     assert err(to_np(zd), dz_ref, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
 
 
+@pytest.mark.parametrize("dtype,N,V", [("bf16", 4, 131072),    # the longest row the register-cached kernel takes (1024 threads x 16 vectors)
+                                       ("bf16", 3, 131080),    # one vector more: the three-pass kernel
+                                       ("f32", 5, 65536), ("f32", 2, 65540),
+                                       ("bf16", 9, 50304), ("bf16", 6, 512), ("bf16", 6, 8)])
+def test_cross_entropy_row_lengths_around_the_cache_limit_and_wide_logit_ranges(dtype, N, V):
+    rng = np.random.default_rng(N * 7 + V)
+    z = rng.standard_normal((N, V)) * 3
+    z[0, : min(V, 16)] += 60.0       # a few dominant logits: everything else underflows next to them
+    z[-1] -= 80.0                    # a row far below zero
+    z[N // 2, V // 2] = 88.0
+    z = _store(z, dtype)
+    y = rng.integers(0, V, N).astype(np.int32)
+    y[0] = 3; y[-1] = V - 1
+    loss_ref, dz_ref = orc.cross_entropy(z, y.astype(np.int64))
+    zd = to_dev(z, dtype); yd = torch.from_numpy(y).to(DEV)
+    out = torch.empty_like(zd); rl = torch.empty(N, device=DEV); loss = torch.empty(1, device=DEV)
+    fax.fax_cross_entropy(CODE[dtype], N, V, zd, yd, out, rl, loss)
+    assert abs(loss.item() - loss_ref) <= 4e-6 * abs(loss_ref)
+    assert err(to_np(out), dz_ref, dtype) <= (1e-5 if dtype == "f32" else 4e-3)
+    assert np.abs(to_np(out).sum(axis=1)).max() <= (5e-6 if dtype == "f32" else 4e-3) / N   # rows of the gradient sum to zero
+
+
 def test_cross_entropy_uniform_logits_give_log_vocab():
     N, V = 5, 51200
     zd = torch.full((N, V), 0.75, dtype=torch.bfloat16, device=DEV)
@@ -264,6 +286,32 @@ def test_adamw_block_step_updates_all_twelve_tensors_like_the_single_tensor_call
     fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, md, vd, gd)), None, hp, 4)
     fax.fax_adamw_step(p1["w1"], m1["w1"], v1["w1"], gd["w1"], None, shapes["w1"], hp, 4)
     assert torch.equal(p1["w1"], pd["w1"])
+
+
+# ------------------------------------------------------------------------- measured ceilings
+def test_probe_kernels_run_and_are_timed():
+    n = 1 << 22
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(4, device=DEV)
+    fax.fax_timing_enable(1)
+    try:
+        fax.fax_probe_copy(src, dst, n)
+        fax.fax_probe_mfma(64, 100, 0, sink)
+        fax.fax_probe_mfma(64, 100, 1, sink)
+        torch.cuda.synchronize()
+        rows = {r["name"]: r for r in fax.fax_timing_report(16)}
+    finally:
+        fax.fax_timing_enable(0)
+    assert torch.equal(src, dst)
+    assert float(sink.abs().max()) == 0.0
+    assert rows["probe_copy"]["work"] == 2.0 * n
+    assert rows["probe_mfma_zero"]["work"] == rows["probe_mfma_random"]["work"] == 64 * 4 * 100 * 16 * 32768.0
+    assert all(rows[k]["ms"] > 0 for k in ("probe_copy", "probe_mfma_zero", "probe_mfma_random"))
+    with pytest.raises(fax.FaxError):
+        fax.fax_probe_copy(src, dst, 24)
+    with pytest.raises(fax.FaxError):
+        fax.fax_probe_mfma(0, 100, 0, sink)
 
 
 # ------------------------------------------------------------------------- per-kernel timing

@@ -107,3 +107,68 @@ def test_gemm_argument_checks():
         fax.fax_gemm(fax.FAX_F32, 0, 0, 128, 128, 64, 4096, 64, 4096, 128, 4096, 128, path=fax.PATH_MFMA, stream=0)
     assert e.value.status == fax.FAX_ERR_UNSUPPORTED
     fax.fax_gemm(fax.FAX_F32, 0, 0, 0, 8, 8, None, 8, None, 8, None, 8, stream=0)       # empty is a no-op
+
+
+def test_adamw_hyper_parameters_are_checked_by_every_entry_point_that_takes_them():
+    import ctypes as C
+    d = _dims()
+    good = fax.block_tensors({n: 4096 for n in fax.TENSOR_NAMES})
+    bad_hps = [fax.FaxAdamW(1e-3, 0.9, 1.0, 1e-8, 0.0),      # beta2 = 1: infinite bias correction
+               fax.FaxAdamW(1e-3, -0.1, 0.999, 1e-8, 0.0),
+               fax.FaxAdamW(1e-3, 0.9, 0.999, -1e-8, 0.0),    # negative epsilon
+               fax.FaxAdamW(float("nan"), 0.9, 0.999, 1e-8, 0.0)]
+    for hp in bad_hps:
+        with pytest.raises(fax.FaxError) as e:
+            fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, hp, 1, stream=0)
+        assert e.value.status == fax.FAX_ERR_INVALID_ARG
+        with pytest.raises(fax.FaxError) as e:
+            fax.fax_adamw_block_step(d, good, good, good, good, None, hp, 1, stream=0)
+        assert e.value.status == fax.FAX_ERR_INVALID_ARG
+    # the train step: same check, before anything is launched (all pointers here are fake)
+    md = fax.FaxModelDims(_dims(), 1, 100, 64, 0)
+    tabs = {"tok_emb": 4096, "pos_emb": 4096, "lnf_g": 4096, "lnf_b": 4096, "blocks": [{n: 4096 for n in fax.TENSOR_NAMES}]}
+    for hp in bad_hps:
+        with pytest.raises(fax.FaxError) as e:
+            fax.fax_train_step(md, tabs, tabs, tabs, tabs, tabs, 4096, 4096, hp, 1, 4096, 4096, 1 << 40, stream=0)
+        assert e.value.status == fax.FAX_ERR_INVALID_ARG
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_train_step(md, tabs, tabs, tabs, tabs, tabs, 4096, 4096, fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.0), 0, 4096, 4096,
+                           1 << 40, stream=0)
+    assert "step" in str(e.value)
+    # NULL output pointers of the size queries
+    lib = C.CDLL(fax.LIB_PATH)
+    lib.fax_eval_workspace_bytes.argtypes = [C.POINTER(fax.FaxModelDims), C.c_void_p]
+    assert lib.fax_eval_workspace_bytes(C.byref(md), None) == fax.FAX_ERR_INVALID_ARG
+    lib.fax_gemm_plan.argtypes = [C.c_int] * 4 + [C.c_void_p]
+    assert lib.fax_gemm_plan(256, 256, 64, 0, None) == fax.FAX_ERR_INVALID_ARG
+
+
+def test_gemm_plan_query():
+    # the d_model = 4096 block: every product on 256 x 256 tiles, no split, no strip
+    for shape in [(8192, 12288, 4096, 0), (8192, 4096, 16384, 0), (4096, 16384, 8192, 1), (16384, 4096, 8192, 1)]:
+        assert fax.fax_gemm_plan(*shape) == (0, 256, 256, 1), shape
+    # a narrow model's weight gradient over 65536 tokens: the contraction is cut into ranges
+    tail, tm, tn, splits = fax.fax_gemm_plan(768, 3072, 65536, 1)
+    assert tail == 0 and splits > 1 and 65536 // 64 // splits >= 8
+    # the bf16-output forms never split
+    assert fax.fax_gemm_plan(768, 3072, 65536, 0)[3] == 1
+    # a vocabulary that is an odd multiple of 128: bulk on 256-wide tiles, last 128 apart
+    assert fax.fax_gemm_plan(65536, 50304, 768, 0)[0] == 2
+    assert fax.fax_gemm_plan(50304, 768, 65536, 1)[0] == 1
+    # no tile class divides the shape: the scalar kernel's job
+    assert fax.fax_gemm_plan(100, 72, 64, 0)[1] == 0
+    with pytest.raises(fax.FaxError):
+        fax.fax_gemm_plan(0, 128, 64)
+
+
+def test_static_cross_entropy_checks_its_arguments_before_any_launch():
+    assert fax.fax_cross_entropy_static_max_rows() == 1 << 18
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_cross_entropy_static(fax.FAX_BF16, (1 << 18) + 1, 512, 4096, 4096, 4096, 4096, stream=0)
+    assert e.value.status == fax.FAX_ERR_WORKSPACE and "262144" in str(e.value)
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_cross_entropy_static(fax.FAX_BF16, 16, 512, None, 4096, 4096, 4096, stream=0)
+    assert e.value.status == fax.FAX_ERR_INVALID_ARG
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_cross_entropy_static(7, 16, 512, 4096, 4096, 4096, 4096, stream=0)
+    assert e.value.status == fax.FAX_ERR_INVALID_ARG
