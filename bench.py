@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (the same C-ABI calls) in a HIP graph and time its replays")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="FAX_FLAG_SINGLE_STREAM: keep the weight gradients on the caller's stream (for comparison)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured MFMA-only and copy-kernel ceilings")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain elementwise copy kernel (reads 256 MiB, writes 128 MiB): a known-size reference "
@@ -68,7 +70,7 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(dtype).contiguous()
 
     dims = fax.block_dims(sh.B, sh.S, sh.D, sh.H, sh.dh, sh.F, code, fax.FAX_GELU_TANH, sh.ln_eps,
-                          fax.FAX_FLAG_TP_PARTIAL if tp_share else 0)
+                          (fax.FAX_FLAG_TP_PARTIAL if tp_share else 0) | (fax.FAX_FLAG_SINGLE_STREAM if args.single_stream else 0))
     hp = fax.FaxAdamW(**ADAMW_DEFAULT)
     T = sh.T
 

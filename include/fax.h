@@ -52,6 +52,15 @@ enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
 
 /* FaxBlockDims.flags */
 #define FAX_FLAG_TP_PARTIAL 1u /* also emit the pre-reduction partial sums (Sec. 3.2) */
+/* fax_block_bwd (and the backward pass inside fax_train_step) by default enqueues the four
+ * weight-gradient products and the folds of the LayerNorm parameter gradients on a stream of the
+ * library's own, forked from the caller's stream when the call begins and joined back into it
+ * before the call returns: they depend on nothing later in the chain of input gradients and run
+ * beside it.  To the caller the call behaves as if everything were on its stream (ordered after
+ * what was enqueued before, before what is enqueued after).  The stream and its events are
+ * created once per device, on first use; no device memory is involved.  With this flag
+ * everything is enqueued on the caller's stream only. */
+#define FAX_FLAG_SINGLE_STREAM 2u
 
 /* FaxModelDims.flags */
 #define FAX_FLAG_SKIP_UPDATE 1u /* fax_train_step: stop after the gradients */
@@ -72,7 +81,7 @@ typedef struct FaxBlockDims {
   int32_t dtype;  /* FAX_F32 | FAX_BF16 */
   int32_t gelu;   /* FAX_GELU_TANH | FAX_GELU_ERF */
   float ln_eps;   /* LayerNorm epsilon, added to the biased variance */
-  uint32_t flags;
+  uint32_t flags; /* FAX_FLAG_TP_PARTIAL | FAX_FLAG_SINGLE_STREAM */
 } FaxBlockDims;
 
 /* The twelve parameter tensors of a block, or twelve buffers shaped like them

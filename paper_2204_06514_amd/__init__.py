@@ -19,6 +19,7 @@ FAX_OK, FAX_ERR_INVALID_ARG, FAX_ERR_UNSUPPORTED, FAX_ERR_WORKSPACE, FAX_ERR_HIP
 FAX_F32, FAX_BF16 = 0, 1
 FAX_GELU_TANH, FAX_GELU_ERF = 0, 1
 FAX_FLAG_TP_PARTIAL = 1
+FAX_FLAG_SINGLE_STREAM = 2
 FAX_FLAG_SKIP_UPDATE = 1
 FAX_FLAG_ACCUMULATE = 2
 FAX_FLAG_DETERMINISTIC = 4

@@ -132,7 +132,7 @@ static void saved_layout(const FaxBlockDims& d, FaxSavedLayout* L) {
 
 struct BwdWs {
   FaxBwdLayout pub;
-  size_t delta, red, splitk, total;
+  size_t delta, red, red_ln1, red_side, splitk, total;
 };
 
 static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
@@ -152,6 +152,8 @@ static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
   size_t red = ln_bwd_ws_bytes(d.D);
   if (colsum_ws_bytes((int)widest) > red) red = colsum_ws_bytes((int)widest);
   W->red = take(red);
+  W->red_ln1 = take(ln_bwd_ws_bytes(d.D));  // LN1's partial rows: LN2's may still await their fold on the second stream
+  W->red_side = take(colsum_ws_bytes((int)widest));  // column-sum scratch of the weight-gradient stream
   // scratch for the weight-gradient products whose contraction gets split (narrow models)
   const int T = (int)z.T, D = (int)z.D, Hd = (int)z.Hd, F = (int)z.F;
   size_t sk = gemm_split_ws_bytes(F, D, T);
@@ -293,6 +295,40 @@ static int block_fwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   return FAX_OK;
 }
 
+// ---- a second stream for the weight gradients --------------------------------------------------
+// In the backward pass the weight-gradient product of a projection and its input-gradient product
+// read the same upstream gradient and do not depend on each other; only the input gradients are on
+// the path to the next kernel.  With few tokens (the 2048-token shares) neither fills the chip: a
+// GEMM has 80 to 160 tiles for 256 CUs and attention a few dozen workgroups.  The four weight
+// gradients are then enqueued on a stream of the library's own, forked from and joined back into
+// the caller's stream with events inside the same call, so that they run beside the chain of
+// input gradients.  Seen from the caller nothing changes: everything the call enqueues is
+// ordered after earlier work on the caller's stream and before later work on it.
+struct SideStream {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, du = nullptr, dx1 = nullptr, dqkv = nullptr, ln2 = nullptr, ln1 = nullptr, w2_done = nullptr, join = nullptr;
+};
+static std::mutex g_side_mu;
+static SideStream* g_side[64];
+
+static int side_stream(SideStream** out) {
+  int dev = -1;
+  FAX_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) { *out = nullptr; return FAX_OK; }
+  std::lock_guard<std::mutex> lk(g_side_mu);
+  if (!g_side[dev]) {
+    SideStream* n = new SideStream;
+    FAX_HIP(hipStreamCreateWithFlags(&n->s, hipStreamNonBlocking));  // default priority
+    for (hipEvent_t* e : {&n->fork, &n->du, &n->dx1, &n->dqkv, &n->ln2, &n->ln1, &n->w2_done, &n->join})
+      FAX_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    g_side[dev] = n;
+  }
+  *out = g_side[dev];
+  return FAX_OK;
+}
+
+static bool use_side_stream(const FaxBlockDims& d) { return !(d.flags & FAX_FLAG_SINGLE_STREAM); }
+
 // ---- block backward -------------------------------------------------------------------------
 static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const void* x, const void* dy,
                           const char* saved, void* dx, const FaxBlockTensors& gr, bool acc, char* ws, hipStream_t s) {
@@ -307,14 +343,18 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   float* delta = (float*)(ws + W.delta);
   void* red = ws + W.red;
 
+  SideStream* side = nullptr;
+  if (use_side_stream(d)) FAX_TRY(side_stream(&side));
+  hipStream_t sw = side ? side->s : s;  // where the weight gradients go
+  void* red_w = side ? (void*)(ws + W.red_side) : red;
   auto wgrad = [&](const void* act, int lda, int Kdim, const void* grad, int ldb, int Ndim, void* out, void* bias_grad) {
     GemmArgs g;  // out[Kdim, Ndim] (+)= act^T grad, contraction over the T rows; bias_grad[Ndim] (+)= column sums of grad
     g.dtype = d.dtype; g.ta = true; g.tb = false;
     g.M = Kdim; g.N = Ndim; g.K = T;
     g.A = act; g.lda = lda; g.B = grad; g.ldb = ldb; g.C = out; g.ldc = Ndim; g.c_f32 = true; g.accumulate = acc;
-    g.colsum = (float*)bias_grad; g.colsum_ws = red;
+    g.colsum = (float*)bias_grad; g.colsum_ws = red_w;
     g.split_ws = W.splitk < W.total ? ws + W.splitk : nullptr;
-    return gemm(g, s);
+    return gemm(g, sw);
   };
   auto dgrad = [&](const void* grad, int lda, int Ndim, const void* w, int ldw, int Kdim, void* out) {
     GemmArgs g;  // out[T, Kdim] = grad[T, Ndim] w[Kdim, Ndim]^T
@@ -323,32 +363,54 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
     g.A = grad; g.lda = lda; g.B = w; g.ldb = ldw; g.C = out; g.ldc = Kdim;
     return g;
   };
+  // main stream records `e` once the tensor the next weight gradient reads is complete; the side stream waits for it
+  auto hand_over = [&](hipEvent_t SideStream::*e) -> int {
+    if (!side) return FAX_OK;
+    FAX_HIP(hipEventRecord(side->*e, s));
+    FAX_HIP(hipStreamWaitEvent(side->s, side->*e, 0));
+    return FAX_OK;
+  };
 
   // feed-forward output projection
+  FAX_TRY(hand_over(&SideStream::fork));  // everything enqueued before this call (dy, saved, ...) is visible to the side stream
   FAX_TRY(wgrad(saved + L.a, F, F, dy, D, D, gr.w2, gr.b2));
+  if (side) FAX_HIP(hipEventRecord(side->w2_done, side->s));
   {
     GemmArgs g = dgrad(dy, D, D, p.w2, D, F, du);  // du = (dy W2^T) * gelu'(u)
     g.epi = EPI_DGELU; g.U = saved + L.dgelu; g.ldu = F;
     FAX_TRY(gemm(g, s));
   }
   // feed-forward input projection
+  FAX_TRY(hand_over(&SideStream::du));
   FAX_TRY(wgrad(saved + L.h2, D, D, du, F, F, gr.w1, gr.b1));
   FAX_TRY(gemm(dgrad(du, F, F, p.w1, F, D, dh2), s));
   // LN2 and the residual branch: dx1 = dy + LN2'(dh2)
   FAX_TRY(ln_bwd(d.dtype, T, D, dh2, saved + L.x1, (const float*)(saved + L.mu2), (const float*)(saved + L.rstd2),
-                 p.ln2_g, dy, dx1, (float*)gr.ln2_g, (float*)gr.ln2_b, acc, red, s));
+                 p.ln2_g, dy, dx1, (float*)gr.ln2_g, (float*)gr.ln2_b, acc, red, s, side ? side->s : nullptr,
+                 side ? side->ln2 : nullptr));
   // attention output projection
+  FAX_TRY(hand_over(&SideStream::dx1));
   FAX_TRY(wgrad(saved + L.ctx, Hd, Hd, dx1, D, D, gr.wo, gr.bo));
   FAX_TRY(gemm(dgrad(dx1, D, D, p.wo, D, Hd, dctx), s));
   // attention
   FAX_TRY(attention_bwd(d.dtype, d.B, d.S, d.H, d.dh, saved + L.qkv, saved + L.ctx, (const float*)(saved + L.lse), dctx,
                         dqkv, delta, PATH_AUTO, s));
   // QKV projection
+  FAX_TRY(hand_over(&SideStream::dqkv));
   FAX_TRY(wgrad(saved + L.h1, D, D, dqkv, 3 * Hd, 3 * Hd, gr.wqkv, gr.bqkv));
   FAX_TRY(gemm(dgrad(dqkv, 3 * Hd, 3 * Hd, p.wqkv, 3 * Hd, D, dh1), s));
-  // LN1 and the residual branch: dx = dx1 + LN1'(dh1)
+  // LN1 and the residual branch: dx = dx1 + LN1'(dh1).  dx may be the buffer dy came in: the first
+  // weight gradient, which reads dy, has to be through with it.
+  if (side) FAX_HIP(hipStreamWaitEvent(s, side->w2_done, 0));
   FAX_TRY(ln_bwd(d.dtype, T, D, dh1, x, (const float*)(saved + L.mu1), (const float*)(saved + L.rstd1), p.ln1_g, dx1,
-                 dx, (float*)gr.ln1_g, (float*)gr.ln1_b, acc, red, s));
+                 dx, (float*)gr.ln1_g, (float*)gr.ln1_b, acc, side ? (void*)(ws + W.red_ln1) : red, s, side ? side->s : nullptr,
+                 side ? side->ln1 : nullptr));
+  // join: later work on the caller's stream (the next block, the update) sees every gradient, and the
+  // workspace is free again
+  if (side) {
+    FAX_HIP(hipEventRecord(side->join, side->s));
+    FAX_HIP(hipStreamWaitEvent(s, side->join, 0));
+  }
   return FAX_OK;
 }
 

@@ -85,7 +85,10 @@ int ln_fwd(int dtype, int rows, int D, const void* x, const void* gamma, const v
 size_t ln_bwd_ws_bytes(int D);
 int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const float* mu, const float* rstd,
            const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta, bool accumulate,
-           void* ws, hipStream_t s);
+           void* ws, hipStream_t s, hipStream_t fold_s = nullptr, hipEvent_t handover = nullptr);
+// (fold_s, handover: optionally a second stream for the fold of the partial rows, which feeds only
+// dgamma / dbeta, and an event to order it behind the row kernel; `ws` then stays in use until that
+// stream has run the fold)
 size_t colsum_ws_bytes(int N);
 // out[i] (+)= sum_p partial[p * n + i], p < parts, in that order
 // out[i] (+)= sum over p < parts of partial[p * n + i]; optionally a second stack (nb elements per part) into

@@ -493,7 +493,7 @@ size_t colsum_ws_bytes(int N) { return (size_t)CS_PARTS * (size_t)N * sizeof(flo
 template <typename T>
 static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, const float* rstd, const T* gamma,
                     const T* dres, T* dx, float* dgamma, float* dbeta, bool accumulate, float* partial,
-                    hipStream_t s) {
+                    hipStream_t s, hipStream_t fold_s, hipEvent_t handover) {
   constexpr int VN = Vec16<T>::N;
   const int nvec = D / VN;
   const int gb = (D + 63) / 64;
@@ -524,10 +524,18 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
     else FAX_LN_BWD_FUSED(256, LN_MAXV);
 #undef FAX_LN_BWD_FUSED
     FAX_LAUNCH_CHECK("ln_bwd_fused");
+    // The fold only feeds the parameter gradients, nothing further down the backward pass: given a
+    // second stream it goes there, behind an event that marks the partial rows complete.
+    hipStream_t fs = s;
+    if (fold_s && fold_s != s && handover) {
+      FAX_HIP(hipEventRecord(handover, s));
+      FAX_HIP(hipStreamWaitEvent(fold_s, handover, 0));
+      fs = fold_s;
+    }
     if (D % 4 == 0 && ((reinterpret_cast<uintptr_t>(dgamma) | reinterpret_cast<uintptr_t>(dbeta)) & 15) == 0)
-      hipLaunchKernelGGL(fold_partials4_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
+      hipLaunchKernelGGL(fold_partials4_kernel, dim3(gb, 2), dim3(256), 0, fs, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
     else
-      hipLaunchKernelGGL(fold_partials_kernel, dim3(gb, 2), dim3(256), 0, s, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
+      hipLaunchKernelGGL(fold_partials_kernel, dim3(gb, 2), dim3(256), 0, fs, parts, D, partial, dgamma, dbeta, accumulate ? 1 : 0);
     FAX_LAUNCH_CHECK("ln_bwd_fold");
     return FAX_OK;
   }
@@ -545,14 +553,14 @@ static int ln_bwd_t(int rows, int D, const T* dh, const T* x, const float* mu, c
 
 int ln_bwd(int dtype, int rows, int D, const void* dh, const void* x, const float* mu, const float* rstd,
            const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta, bool accumulate, void* ws,
-           hipStream_t s) {
+           hipStream_t s, hipStream_t fold_s, hipEvent_t handover) {
   if (rows == 0) return FAX_OK;
   Timed t_("layernorm_bwd", WORK_BYTE, (dres ? 4.0 : 3.0) * rows * D * (dtype == FAX_F32 ? 4.0 : 2.0) + 8.0 * rows, s);
   if (dtype == FAX_F32)
     return ln_bwd_t<float>(rows, D, (const float*)dh, (const float*)x, mu, rstd, (const float*)gamma, (const float*)dres,
-                           (float*)dx, dgamma, dbeta, accumulate, (float*)ws, s);
+                           (float*)dx, dgamma, dbeta, accumulate, (float*)ws, s, fold_s, handover);
   return ln_bwd_t<bf16_t>(rows, D, (const bf16_t*)dh, (const bf16_t*)x, mu, rstd, (const bf16_t*)gamma,
-                          (const bf16_t*)dres, (bf16_t*)dx, dgamma, dbeta, accumulate, (float*)ws, s);
+                          (const bf16_t*)dres, (bf16_t*)dx, dgamma, dbeta, accumulate, (float*)ws, s, fold_s, handover);
 }
 
 int colsum(int dtype, int rows, int N, const void* a, int lda, float* out, bool accumulate, void* ws, hipStream_t s) {

@@ -17,15 +17,15 @@ from test_gpu_train import run_train_step, _walk
 pytestmark = pytest.mark.gpu
 
 
-def _block_twice(sh, seed):
+def _block_twice(sh, seed, flags=(0, 0)):
     p, x, dy = make_block_inputs(sh, seed=seed, generic=True)
-    dims = dims_of(sh, fax.FAX_FLAG_TP_PARTIAL)
     pd = {k: to_dev(p[k], sh.dtype) for k in PARAM_NAMES}
     xd, dyd = to_dev(x, sh.dtype), to_dev(dy, sh.dtype)
-    lay = fax.fax_block_saved_layout(dims)
-    wsb = fax.fax_block_workspace_bytes(dims)
+    lay = fax.fax_block_saved_layout(dims_of(sh))
+    wsb = fax.fax_block_workspace_bytes(dims_of(sh))
     runs = []
-    for _ in range(2):
+    for extra in flags:
+        dims = dims_of(sh, fax.FAX_FLAG_TP_PARTIAL | extra)
         saved = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
         ws = torch.zeros(wsb, dtype=torch.uint8, device=DEV)
         y, pa, pm, dx = (torch.empty_like(xd) for _ in range(4))
@@ -47,6 +47,33 @@ def test_block_forward_and_backward_are_bit_reproducible(sh):
     a, b = _block_twice(sh, seed=7)
     for k in a:
         assert torch.equal(a[k], b[k]), k
+
+
+@pytest.mark.parametrize("sh", [get_config("cfg1"),
+                                BlockShape(B=2, S=1024, D=256, H=2, dh=128, F=512, dtype="bf16", sigma_w=0.02)],
+                         ids=lambda s: "%s_D%d_S%d" % (s.dtype, s.D, s.S))
+def test_the_second_stream_changes_no_bit(sh):
+    """Weight gradients on the library's own stream (the default) against FAX_FLAG_SINGLE_STREAM:
+    the same kernels in a different enqueue order, so every output must agree bit for bit; and
+    dx written over dy, which the first weight gradient reads on the other stream."""
+    a, b = _block_twice(sh, seed=8, flags=(0, fax.FAX_FLAG_SINGLE_STREAM))
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    p, x, dy = make_block_inputs(sh, seed=8, generic=True)
+    dims = dims_of(sh, fax.FAX_FLAG_TP_PARTIAL)
+    pd = {k: to_dev(p[k], sh.dtype) for k in PARAM_NAMES}
+    xd, dyd = to_dev(x, sh.dtype), to_dev(dy, sh.dtype)
+    saved = torch.zeros(fax.fax_block_saved_layout(dims).total, dtype=torch.uint8, device=DEV)
+    wsb = fax.fax_block_workspace_bytes(dims)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=DEV)
+    y, pa, pm = (torch.empty_like(xd) for _ in range(3))
+    gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
+    fax.fax_block_fwd(dims, pd, xd, y, saved, pa, pm, ws, wsb)
+    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dyd, gd, 0, ws, wsb)      # dx aliases dy
+    torch.cuda.synchronize()
+    assert torch.equal(dyd, a["dx"])
+    for k in PARAM_NAMES:
+        assert torch.equal(gd[k], a["d" + k]), k
 
 
 CASES = [
