@@ -58,8 +58,10 @@ enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
  * before the call returns: they depend on nothing later in the chain of input gradients and run
  * beside it.  To the caller the call behaves as if everything were on its stream (ordered after
  * what was enqueued before, before what is enqueued after).  The stream and its events are
- * created once per device, on first use; no device memory is involved.  With this flag
- * everything is enqueued on the caller's stream only. */
+ * created once per device, on first use; no device memory is involved.  (When every product of
+ * the backward pass fills the chip a whole number of times there is nothing to run beside, and
+ * the library keeps to the caller's stream by itself.)  With this flag everything is enqueued on
+ * the caller's stream only. */
 #define FAX_FLAG_SINGLE_STREAM 2u
 
 /* FaxModelDims.flags */

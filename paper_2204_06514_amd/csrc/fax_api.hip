@@ -327,7 +327,26 @@ static int side_stream(SideStream** out) {
   return FAX_OK;
 }
 
-static bool use_side_stream(const FaxBlockDims& d) { return !(d.flags & FAX_FLAG_SINGLE_STREAM); }
+// When every product of the backward pass is a whole number of rounds of one workgroup per CU
+// (the 4096-wide block: 256 to 2048 tiles each), the second stream has nothing to fill and the
+// kernels would only take turns: everything then stays on the caller's stream.
+static bool use_side_stream(const FaxBlockDims& d) {
+  if (d.flags & FAX_FLAG_SINGLE_STREAM) return false;
+  if (d.dtype != FAX_BF16) return true;
+  Sizes z(d);
+  const int T = (int)z.T, D = d.D, Hd = (int)z.Hd, F = d.F;
+  const int shapes[8][4] = {{F, D, T, 1}, {D, F, T, 1}, {Hd, D, T, 1}, {D, 3 * Hd, T, 1},
+                            {T, F, D, 0}, {T, D, F, 0}, {T, Hd, D, 0}, {T, D, 3 * Hd, 0}};
+  constexpr long long kCUs = 256;
+  for (const auto& g : shapes) {
+    int tail = 0;
+    const GemmSplitPlan p = gemm_plan_query(g[0], g[1], g[2], g[3] != 0, &tail);
+    if (tail || p.tile_m == 0) return true;
+    const long long items = (long long)(g[0] / p.tile_m) * (g[1] / p.tile_n) * p.splits;
+    if (items % kCUs) return true;
+  }
+  return false;
+}
 
 // ---- block backward -------------------------------------------------------------------------
 static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const void* x, const void* dy,
