@@ -38,6 +38,8 @@ def parse():
                     help="capture one step (the same C-ABI calls) in a HIP graph and time its replays")
     ap.add_argument("--single-stream", action="store_true",
                     help="FAX_FLAG_SINGLE_STREAM: keep the weight gradients on the caller's stream (for comparison)")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="FAX_FLAG_DETERMINISTIC (train-step workloads): ordered reduction for the embedding gradient")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured MFMA-only and copy-kernel ceilings")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run a plain elementwise copy kernel (reads 256 MiB, writes 128 MiB): a known-size reference "
@@ -89,7 +91,7 @@ def main():
         m = like(lambda t: torch.zeros(t.shape, dtype=torch.float32, device=dev))
         v = like(lambda t: torch.zeros(t.shape, dtype=torch.float32, device=dev))
         grads = like(lambda t: torch.empty(t.shape, dtype=torch.float32, device=dev))
-        md = fax.FaxModelDims(dims, sh.L, cfg.V, cfg.S_max, 0)
+        md = fax.FaxModelDims(dims, sh.L, cfg.V, cfg.S_max, fax.FAX_FLAG_DETERMINISTIC if args.deterministic else 0)
         wsb = fax.fax_train_workspace_bytes(md)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
         tokd, labd = torch.from_numpy(tok).to(dev), torch.from_numpy(lab).to(dev)
