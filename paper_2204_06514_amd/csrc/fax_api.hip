@@ -132,7 +132,7 @@ static void saved_layout(const FaxBlockDims& d, FaxSavedLayout* L) {
 
 struct BwdWs {
   FaxBwdLayout pub;
-  size_t delta, red, red_ln1, red_side, splitk, total;
+  size_t delta, delta2, red, red_ln1, red_side, splitk, total;
 };
 
 static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
@@ -146,6 +146,7 @@ static void bwd_layout(const FaxBlockDims& d, BwdWs* W) {
   W->pub.dqkv = take(z.T * 3 * z.Hd * z.es);
   W->pub.dh1 = take(z.T * z.D * z.es);
   W->delta = take((size_t)d.B * d.H * d.S * 4);
+  W->delta2 = take((size_t)d.B * d.H * d.S * 4);  // the dQ kernel's own copy when delta comes from a kernel of its own
   size_t widest = z.D;
   if (z.F > widest) widest = z.F;
   if (3 * z.Hd > widest) widest = 3 * z.Hd;
@@ -240,7 +241,8 @@ static int attention_fwd(int dtype, int B, int S, int H, int dh, const void* qkv
 }
 
 static int attention_bwd(int dtype, int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
-                         const void* dctx, void* dqkv, float* delta, int path, hipStream_t s) {
+                         const void* dctx, void* dqkv, float* delta, int path, hipStream_t s,
+                         const AttnBwdSplit* split = nullptr) {
   const bool ok = attn_mfma_supported(dtype, B, S, H, dh);
   if (path == PATH_MFMA && !ok) {
     set_error("attention: dtype %d, S=%d, dh=%d is not covered by the MFMA kernel", dtype, S, dh);
@@ -248,7 +250,7 @@ static int attention_bwd(int dtype, int B, int S, int H, int dh, const void* qkv
   }
   const bool mfma = ok && path != PATH_SIMT;
   Timed t_(mfma ? "attention_bwd_mfma" : "attention_bwd_scalar", WORK_FLOP, 4.0 * B * H * (double)S * S * dh, s);
-  if (mfma) return attn_bwd_mfma(B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s);
+  if (mfma) return attn_bwd_mfma(B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s, split);
   return attn_bwd_simt(dtype, B, S, H, dh, qkv, ctx, lse, dctx, dqkv, delta, s);
 }
 
@@ -306,7 +308,8 @@ static int block_fwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
 // ordered after earlier work on the caller's stream and before later work on it.
 struct SideStream {
   hipStream_t s = nullptr;
-  hipEvent_t fork = nullptr, du = nullptr, dx1 = nullptr, dqkv = nullptr, ln2 = nullptr, ln1 = nullptr, w2_done = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, du = nullptr, dx1 = nullptr, dqkv = nullptr, ln2 = nullptr, ln1 = nullptr, w2_done = nullptr, join = nullptr,
+             attn_fork = nullptr, attn_join = nullptr;
 };
 static std::mutex g_side_mu;
 static SideStream* g_side[64];
@@ -319,7 +322,7 @@ static int side_stream(SideStream** out) {
   if (!g_side[dev]) {
     SideStream* n = new SideStream;
     FAX_HIP(hipStreamCreateWithFlags(&n->s, hipStreamNonBlocking));  // default priority
-    for (hipEvent_t* e : {&n->fork, &n->du, &n->dx1, &n->dqkv, &n->ln2, &n->ln1, &n->w2_done, &n->join})
+    for (hipEvent_t* e : {&n->fork, &n->du, &n->dx1, &n->dqkv, &n->ln2, &n->ln1, &n->w2_done, &n->join, &n->attn_fork, &n->attn_join})
       FAX_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     g_side[dev] = n;
   }
@@ -412,8 +415,10 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
   FAX_TRY(wgrad(saved + L.ctx, Hd, Hd, dx1, D, D, gr.wo, gr.bo));
   FAX_TRY(gemm(dgrad(dx1, D, D, p.wo, D, Hd, dctx), s));
   // attention
+  const AttnBwdSplit split{(float*)(ws + W.delta2), side ? side->s : nullptr, side ? side->attn_fork : nullptr,
+                           side ? side->attn_join : nullptr};
   FAX_TRY(attention_bwd(d.dtype, d.B, d.S, d.H, d.dh, saved + L.qkv, saved + L.ctx, (const float*)(saved + L.lse), dctx,
-                        dqkv, delta, PATH_AUTO, s));
+                        dqkv, delta, PATH_AUTO, s, &split));
   // QKV projection
   FAX_TRY(hand_over(&SideStream::dqkv));
   FAX_TRY(wgrad(saved + L.h1, D, D, dqkv, 3 * Hd, 3 * Hd, gr.wqkv, gr.bqkv));

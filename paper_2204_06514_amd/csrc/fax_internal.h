@@ -107,8 +107,16 @@ int attn_bwd_simt(int dtype, int B, int S, int H, int dh, const void* qkv, const
 int attn_delta(int dtype, int B, int S, int H, int dh, const void* ctx, const void* dctx, float* delta, hipStream_t s);
 bool attn_mfma_supported(int dtype, int B, int S, int H, int dh);
 int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float* lse, hipStream_t s);
+// Optional: scratch for the dQ kernel's own copy of delta ([B,H,S] fp32) and a second stream with two
+// events; given them, and few enough workgroups (attn_bwd_side_by_side), dQ and dK/dV run side by side.
+struct AttnBwdSplit {
+  float* delta_scratch;
+  hipStream_t side;
+  hipEvent_t fork, join;
+};
+bool attn_bwd_side_by_side(int B, int S, int H);
 int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse,
-                  const void* dctx, void* dqkv, float* delta, hipStream_t s);
+                  const void* dctx, void* dqkv, float* delta, hipStream_t s, const AttnBwdSplit* split = nullptr);
 
 // ---- loss, embedding, optimizer ---------------------------------------------------------------
 // dlogits = grad_scale (softmax - onehot) / N, may alias logits, NULL for the loss alone

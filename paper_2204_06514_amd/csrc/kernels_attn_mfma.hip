@@ -492,29 +492,60 @@ int attn_fwd_mfma(int B, int S, int H, int dh, const void* qkv, void* ctx, float
 
 template <int DH>
 static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx,
-                 bf16_t* dqkv, float* delta, hipStream_t s) {
+                 bf16_t* dqkv, float* delta, hipStream_t s, const AttnBwdSplit* split) {
   constexpr size_t lds_q = 2 * (2 * (size_t)TR * DH * 2);  // two stages of K tile | V tile
   const dim3 grid(((S / 128 + 1) / 2) * B * H);
-  // dQ first: it also produces delta, which the dK/dV kernel reads
   FAX_TRY(set_lds(attn_bwd_dq_mfma_kernel<DH>, lds_q));
-  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
-  if constexpr (DH == 64) {
-    constexpr size_t lds_kv = 2 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // two stages of Q tile | dO tile | lse, delta
-    FAX_TRY(set_lds(attn_bwd_dkv_phased_mfma_kernel<DH>, lds_kv));
-    hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kv, s, S, H, B * H, qkv, lse, delta, dctx,
-                       dqkv);
-  } else {
-    FAX_TRY(attn_bwd_dkv128_mfma(B, S, H, qkv, lse, delta, dctx, dqkv, s));
+  auto dkv = [&](hipStream_t st) -> int {
+    if constexpr (DH == 64) {
+      constexpr size_t lds_kv = 2 * (2 * (size_t)TR * DH * 2 + 4 * 256);  // two stages of Q tile | dO tile | lse, delta
+      FAX_TRY(set_lds(attn_bwd_dkv_phased_mfma_kernel<DH>, lds_kv));
+      hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kv, st, S, H, B * H, qkv, lse, delta, dctx,
+                         dqkv);
+    } else {
+      FAX_TRY(attn_bwd_dkv128_mfma(B, S, H, qkv, lse, delta, dctx, dqkv, st));
+    }
+    return FAX_OK;
+  };
+  // Few workgroups (a tensor-parallel share at batch 1: 40 to 128 of them on 256 CUs): the dQ and the
+  // dK/dV kernel fit on the chip side by side.  What ties them together is delta, which the dQ
+  // kernel produces as it goes; a small kernel of its own computes it first, the dQ kernel writes
+  // its copy to scratch, and with a second stream the two kernels run at the same time.  Whether
+  // this form is used depends on the shape only, so that one or two streams give the same bits.
+  if (split && split->delta_scratch && attn_bwd_side_by_side(B, S, H)) {
+    FAX_TRY(attn_delta(FAX_BF16, B, S, H, DH, ctx, dctx, delta, s));
+    const bool two = split->side && split->fork && split->join;
+    if (two) {
+      FAX_HIP(hipEventRecord(split->fork, s));
+      FAX_HIP(hipStreamWaitEvent(split->side, split->fork, 0));
+      FAX_TRY(dkv(split->side));
+      FAX_HIP(hipEventRecord(split->join, split->side));
+    }
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx,
+                       split->delta_scratch, dqkv);
+    if (two) FAX_HIP(hipStreamWaitEvent(s, split->join, 0));
+    else FAX_TRY(dkv(s));
+    FAX_LAUNCH_CHECK("attn_bwd_mfma");
+    return FAX_OK;
   }
+  // dQ first: it also produces delta, which the dK/dV kernel reads
+  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<DH>), grid, dim3(256), lds_q, s, S, H, B * H, qkv, lse, ctx, dctx, delta, dqkv);
+  FAX_TRY(dkv(s));
   FAX_LAUNCH_CHECK("attn_bwd_mfma");
   return FAX_OK;
 }
 
+// dK/dV runs one workgroup per CU, dQ two: side by side they need 1.5 CUs per pair of row tiles.
+bool attn_bwd_side_by_side(int B, int S, int H) {
+  const long long n = (long long)((S / 128 + 1) / 2) * B * H;
+  return 3 * n <= 2 * 256;
+}
+
 int attn_bwd_mfma(int B, int S, int H, int dh, const void* qkv, const void* ctx, const float* lse, const void* dctx,
-                  void* dqkv, float* delta, hipStream_t s) {
+                  void* dqkv, float* delta, hipStream_t s, const AttnBwdSplit* split) {
   if (dh == 64)
-    return bwd_t<64>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s);
-  return bwd_t<128>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s);
+    return bwd_t<64>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s, split);
+  return bwd_t<128>(B, S, H, (const bf16_t*)qkv, (const bf16_t*)ctx, lse, (const bf16_t*)dctx, (bf16_t*)dqkv, delta, s, split);
 }
 
 }  // namespace fax
