@@ -58,7 +58,10 @@ enum { FAX_GELU_TANH = 0, FAX_GELU_ERF = 1 };
  * before the call returns: they depend on nothing later in the chain of input gradients and run
  * beside it.  To the caller the call behaves as if everything were on its stream (ordered after
  * what was enqueued before, before what is enqueued after).  The stream and its events are
- * created once per device, on first use; no device memory is involved.  (When every product of
+ * created once per device, on first use (not under stream capture: make one call before
+ * capturing), and live until the process ends; no device memory is involved.  Host threads that
+ * call into the library on the same device share that stream: their calls are enqueued one after
+ * the other on it.  (When every product of
  * the backward pass fills the chip a whole number of times there is nothing to run beside, and
  * the library keeps to the caller's stream by itself.)  With this flag everything is enqueued on
  * the caller's stream only. */

@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfax.so")
 
 SOURCES = ["fax_api.hip", "kernels_norm.hip", "kernels_gemm_simt.hip", "kernels_gemm_mfma.hip",
-           "kernels_attn_simt.hip", "kernels_attn_mfma.hip", "kernels_attn_dkv128.hip", "kernels_loss_opt.hip",
+           "kernels_attn_simt.hip", "kernels_attn_mfma.hip", "kernels_attn_dkv16.hip", "kernels_loss_opt.hip",
            "analyze.hip", "probes.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
@@ -34,9 +34,8 @@ def _hipcc():
 # Per-file additions.  The attention kernels run their softmax arithmetic on MFMA results: with the
 # accumulators in AGPRs (the compiler's default under register pressure) every score costs an extra
 # copy instruction on the vector unit, which bounds those kernels; the VGPR form avoids most copies.
-# (Not for kernels_attn_dkv128.hip: its kernel has a SIMD's whole register file and keeps 128
-# accumulator registers in AGPRs on purpose.)
-EXTRA = {"kernels_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA = {"kernels_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "kernels_attn_dkv16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src):

@@ -307,6 +307,7 @@ static int block_fwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
 // input gradients.  Seen from the caller nothing changes: everything the call enqueues is
 // ordered after earlier work on the caller's stream and before later work on it.
 struct SideStream {
+  std::mutex mu;  // held while one call enqueues: the events are shared, so record/wait pairs of two host threads must not interleave
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, du = nullptr, dx1 = nullptr, dqkv = nullptr, ln2 = nullptr, ln1 = nullptr, w2_done = nullptr, join = nullptr,
              attn_fork = nullptr, attn_join = nullptr;
@@ -367,6 +368,8 @@ static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const
 
   SideStream* side = nullptr;
   if (use_side_stream(d)) FAX_TRY(side_stream(&side));
+  std::unique_lock<std::mutex> side_lock;
+  if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
   hipStream_t sw = side ? side->s : s;  // where the weight gradients go
   void* red_w = side ? (void*)(ws + W.red_side) : red;
   auto wgrad = [&](const void* act, int lda, int Kdim, const void* grad, int ldb, int Ndim, void* out, void* bias_grad) {

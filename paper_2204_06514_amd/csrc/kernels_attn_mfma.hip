@@ -31,9 +31,9 @@
 
 namespace fax {
 
-// dK, dV at DH = 128: kernels_attn_dkv128.hip (compiled with other code-generation options)
-int attn_bwd_dkv128_mfma(int B, int S, int H, const bf16_t* qkv, const float* lse, const float* delta, const bf16_t* dctx,
-                         bf16_t* dqkv, hipStream_t s);
+// dK, dV at DH = 128: kernels_attn_dkv16.hip (16 keys per wave, its own LDS swizzle)
+int attn_bwd_dkv16_mfma(int B, int S, int H, const bf16_t* qkv, const float* lse, const float* delta, const bf16_t* dctx,
+                        bf16_t* dqkv, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------------
 // Forward.  Wave w owns queries 128 qt + 32 w .. + 31 (B operand, in registers); 64-key tiles of
@@ -503,7 +503,7 @@ static int bwd_t(int B, int S, int H, const bf16_t* qkv, const bf16_t* ctx, cons
       hipLaunchKernelGGL((attn_bwd_dkv_phased_mfma_kernel<DH>), grid, dim3(256), lds_kv, st, S, H, B * H, qkv, lse, delta, dctx,
                          dqkv);
     } else {
-      FAX_TRY(attn_bwd_dkv128_mfma(B, S, H, qkv, lse, delta, dctx, dqkv, st));
+      FAX_TRY(attn_bwd_dkv16_mfma(B, S, H, qkv, lse, delta, dctx, dqkv, st));
     }
     return FAX_OK;
   };
