@@ -13,8 +13,11 @@
 // An operand whose M/N index is contiguous ("MC": A stored [K,M], B stored [K,N]) is kept as
 // [k][rows] and fetched with ds_read_b64_tr_b16, the LDS transpose read: 16 lanes pick up four
 // k-rows x 16 columns and each lane receives 4 consecutive k for its own column; two such reads
-// make one MFMA operand.  There the 32-byte column-group index is XOR-ed with (k & 3), which
-// spreads the four k-rows of one read over all banks.  A direct-to-LDS load writes 1024
+// make one MFMA operand.  There the 32-byte column-group index is XOR-ed with mc_swizzle(k), which
+// spreads the eight k-rows that two 16-lane blocks read in one pass over all banks (see there;
+// SQ_LDS_BANK_CONFLICT reads 0 for every flavour of the kernel, where XOR with (k & 3) left 31 %
+// of the LDS cycles in conflicts with one such operand and 49 % with two -- at the same kernel
+// time: these kernels do not wait for the LDS).  A direct-to-LDS load writes 1024
 // consecutive LDS bytes per wave instruction (lane i at +16 i), so both swizzles are applied on
 // the global side: each lane fetches the chunk that belongs at its LDS position.
 //
@@ -51,6 +54,14 @@ struct TileLds {
 // Byte offset, from the slab's first element, of the 16 bytes that belong at LDS byte offset `b`
 // of the slab.  Inverse of the layouts that frag_load() reads.  Does not depend on the slab's
 // position: each lane computes its offsets once and only the (wave-uniform) slab base moves.
+// XOR applied to the 32-byte column-group index of k-row kr of an M/N-contiguous operand.  A
+// transpose read has each 16-lane block fetch four k-rows x 32 bytes; blocks 0 and 1 take the same
+// k-rows at neighbouring groups, blocks 2 and 3 the k-rows eight further down.  Whichever two
+// blocks the LDS serves in one pass, (0, 1) or (0, 2), their eight 32-byte pieces must fall into
+// eight different groups of the 256-byte bank window: bits 0-1 of kr go to bits 1-2 of the XOR
+// (four rows, two apart), bit 3 of kr to bit 0.
+__device__ __forceinline__ int mc_swizzle(int kr) { return ((kr & 3) << 1) | ((kr >> 3) & 1); }
+
 template <int ROWS, bool KC>
 __device__ __forceinline__ unsigned slab_lane_offset(int ld, int b) {
   if (KC) {
@@ -59,7 +70,7 @@ __device__ __forceinline__ unsigned slab_lane_offset(int ld, int b) {
   }
   constexpr int RB = ROWS * 2;  // bytes per k-row
   const int kr = b / RB, pc = (b % RB) >> 4;
-  const int lc = (((pc >> 1) ^ (kr & 3)) << 1) | (pc & 1);
+  const int lc = (((pc >> 1) ^ mc_swizzle(kr)) << 1) | (pc & 1);
   return (unsigned)(kr * ld + (lc << 3)) * 2u;
 }
 
@@ -73,9 +84,9 @@ __device__ __forceinline__ bf16x8 frag_load(const char* lds, int rb, int ks, int
     return __builtin_bit_cast(bf16x8, v);
   } else {
     const int blk = lane >> 4, i = lane & 15;
-    const int kr = ks * 16 + (blk >> 1) * 8 + (i >> 2);  // kr + 4 has the same (k & 3)
+    const int kr = ks * 16 + (blk >> 1) * 8 + (i >> 2);  // kr + 4 has the same swizzle
     const int col = rb + (blk & 1) * 16 + (i & 3) * 4;
-    const char* p = lds + kr * (ROWS * 2) + (((col >> 4) ^ (kr & 3)) << 5) + (col & 15) * 2;
+    const char* p = lds + kr * (ROWS * 2) + (((col >> 4) ^ mc_swizzle(kr)) << 5) + (col & 15) * 2;
     typedef __attribute__((address_space(3))) short4v lds_s4;
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p));
     const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p + 4 * ROWS * 2));
