@@ -137,7 +137,7 @@ def main():
             for l in range(sh.L):
                 fax.fax_block_fwd(dims, pt[l], xs[l], xs[l + 1], saved[l], pa, pm, ws, wsb)
             for l in reversed(range(sh.L)):
-                fax.fax_block_bwd(dims, pt[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gt[l], 0, ws, wsb)
+                fax.fax_block_bwd(dims, pt[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gt[l], 0, None, None, ws, wsb)
             if with_adam:
                 state["t"] += 1
                 for l in range(sh.L):

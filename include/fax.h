@@ -199,12 +199,16 @@ int fax_block_fwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const
  * dy: [B,S,D] upstream gradient; x: the forward input; saved: as filled by fax_block_fwd.
  * dx: [B,S,D] gradient at x (may alias dy).
  * grads: twelve fp32 buffers; accumulate != 0 adds into them, 0 overwrites.
- * After the call the workspace holds the activation gradients at the offsets of
- * fax_block_bwd_layout(), among them the input-gradient partial sums dh1 and dh2.
+ * dh1_partial, dh2_partial: optional [B,S,D] outputs in dims.dtype (device, 16-byte aligned, not
+ *   aliasing any other argument) for the gradients at the outputs of the two LayerNorms,
+ *   dh1 = dqkv Wqkv^T and dh2 = du W1^T: on a tensor-parallel rank these are the partial sums
+ *   that are reduced over the model axis before the LayerNorm backward of the full model
+ *   (Sec. 3.2).  NULL: they are left in the workspace instead, at the offsets of
+ *   fax_block_bwd_layout(), like the other activation gradients of the call.
  */
 int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const void* x, const void* dy,
                   const void* saved, void* dx, const FaxBlockTensors* grads, int accumulate,
-                  void* ws, size_t ws_bytes, void* stream);
+                  void* dh1_partial, void* dh2_partial, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Adam with decoupled weight decay on one tensor of n elements (Table 1 caption: Adam;
@@ -212,9 +216,13 @@ int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const
  *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
  *   p = p (1 - lr wd) - lr (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps).
  * master, m, v: fp32, updated in place (parameters are kept in fp32, Sec. 3).
- * grad: fp32.  lowp: optional bf16 buffer receiving the rounded new parameters (NULL to skip).
+ * grad: n gradients of type grad_dtype, FAX_F32 (what fax_block_bwd and fax_train_step produce)
+ *   or FAX_BF16 (a caller that keeps or communicates gradients in the compute precision); the
+ *   arithmetic is fp32 either way.  FAX_ERR_INVALID_ARG for any other value.
+ * lowp: optional bf16 buffer receiving the rounded new parameters (NULL to skip).
+ * All pointers device, 16-byte aligned.
  */
-int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp, size_t n,
+int fax_adamw_step(void* master, void* m, void* v, const void* grad, int grad_dtype, void* lowp, size_t n,
                    const FaxAdamW* hp, int step, void* stream);
 
 /* The same update on the twelve tensors of a block in one launch (most of them are a few KB: a

@@ -108,8 +108,8 @@ def _load():
         "fax_eval_step": (i32, [P(FaxModelDims), P(FaxModelTensors), vp, vp, vp, vp, sz, vp]),
         "fax_block_fwd": (i32, [P(FaxBlockDims), P(FaxBlockTensors), vp, vp, vp, vp, vp, vp, sz, vp]),
         "fax_block_bwd": (i32, [P(FaxBlockDims), P(FaxBlockTensors), vp, vp, vp, vp, P(FaxBlockTensors), i32,
-                                vp, sz, vp]),
-        "fax_adamw_step": (i32, [vp, vp, vp, vp, vp, sz, P(FaxAdamW), i32, vp]),
+                                vp, vp, vp, sz, vp]),
+        "fax_adamw_step": (i32, [vp, vp, vp, vp, i32, vp, sz, P(FaxAdamW), i32, vp]),
         "fax_adamw_block_step": (i32, [P(FaxBlockDims)] + [P(FaxBlockTensors)] * 5 + [P(FaxAdamW), i32, vp]),
         "fax_train_step": (i32, [P(FaxModelDims)] + [P(FaxModelTensors)] * 5 + [vp, vp, P(FaxAdamW), i32, vp, vp,
                                                                                   sz, vp]),
@@ -255,14 +255,15 @@ def fax_block_fwd(dims, params, x, y, saved, p_attn=None, p_mlp=None, ws=None, w
                               _ptr(p_attn), _ptr(p_mlp), _ptr(ws), ws_bytes, _stream(stream)))
 
 
-def fax_block_bwd(dims, params, x, dy, saved, dx, grads, accumulate, ws, ws_bytes, stream=None):
+def fax_block_bwd(dims, params, x, dy, saved, dx, grads, accumulate, dh1_partial, dh2_partial, ws, ws_bytes, stream=None):
     _check(_lib.fax_block_bwd(C.byref(dims), C.byref(block_tensors(params)), _ptr(x), _ptr(dy), _ptr(saved), _ptr(dx),
-                              C.byref(block_tensors(grads)), int(accumulate), _ptr(ws), ws_bytes, _stream(stream)))
+                              C.byref(block_tensors(grads)), int(accumulate), _ptr(dh1_partial), _ptr(dh2_partial),
+                              _ptr(ws), ws_bytes, _stream(stream)))
 
 
-def fax_adamw_step(master, m, v, grad, lowp, n, hp, step, stream=None):
-    _check(_lib.fax_adamw_step(_ptr(master), _ptr(m), _ptr(v), _ptr(grad), _ptr(lowp), n, C.byref(hp), step,
-                               _stream(stream)))
+def fax_adamw_step(master, m, v, grad, grad_dtype, lowp, n, hp, step, stream=None):
+    _check(_lib.fax_adamw_step(_ptr(master), _ptr(m), _ptr(v), _ptr(grad), int(grad_dtype), _ptr(lowp), n, C.byref(hp),
+                               step, _stream(stream)))
 
 
 def fax_adamw_block_step(dims, master, m, v, grads, lowp, hp, step, stream=None):

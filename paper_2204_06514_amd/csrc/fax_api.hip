@@ -354,15 +354,18 @@ static bool use_side_stream(const FaxBlockDims& d) {
 
 // ---- block backward -------------------------------------------------------------------------
 static int block_bwd_impl(const FaxBlockDims& d, const FaxBlockTensors& p, const void* x, const void* dy,
-                          const char* saved, void* dx, const FaxBlockTensors& gr, bool acc, char* ws, hipStream_t s) {
+                          const char* saved, void* dx, const FaxBlockTensors& gr, bool acc, void* dh1_out,
+                          void* dh2_out, char* ws, hipStream_t s) {
   Sizes z(d);
   FaxSavedLayout L;
   saved_layout(d, &L);
   BwdWs W;
   bwd_layout(d, &W);
   const int T = (int)z.T, D = d.D, Hd = (int)z.Hd, F = d.F;
-  char* du = ws + W.pub.du; char* dh2 = ws + W.pub.dh2; char* dx1 = ws + W.pub.dx1;
-  char* dctx = ws + W.pub.dctx; char* dqkv = ws + W.pub.dqkv; char* dh1 = ws + W.pub.dh1;
+  // dh1, dh2 (the input-gradient partial sums of a tensor-parallel rank) go where the caller wants
+  // them, else into their workspace slots
+  char* du = ws + W.pub.du; char* dh2 = dh2_out ? (char*)dh2_out : ws + W.pub.dh2; char* dx1 = ws + W.pub.dx1;
+  char* dctx = ws + W.pub.dctx; char* dqkv = ws + W.pub.dqkv; char* dh1 = dh1_out ? (char*)dh1_out : ws + W.pub.dh1;
   float* delta = (float*)(ws + W.delta);
   void* red = ws + W.red;
 
@@ -570,8 +573,8 @@ int fax_block_fwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const
 }
 
 int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const void* x, const void* dy,
-                  const void* saved, void* dx, const FaxBlockTensors* grads, int accumulate, void* ws, size_t ws_bytes,
-                  void* stream) {
+                  const void* saved, void* dx, const FaxBlockTensors* grads, int accumulate, void* dh1_partial,
+                  void* dh2_partial, void* ws, size_t ws_bytes, void* stream) {
   FAX_TRY(check_dims(dims));
   FAX_TRY(check_tensors(params, "params"));
   FAX_TRY(check_tensors(grads, "grads"));
@@ -580,18 +583,21 @@ int fax_block_bwd(const FaxBlockDims* dims, const FaxBlockTensors* params, const
   FAX_TRY(check_ptr(saved, "saved"));
   FAX_TRY(check_ptr(dx, "dx"));
   FAX_TRY(check_ptr(ws, "ws"));
+  if (dh1_partial) FAX_TRY(check_ptr(dh1_partial, "dh1_partial"));
+  if (dh2_partial) FAX_TRY(check_ptr(dh2_partial, "dh2_partial"));
   BwdWs W;
   bwd_layout(*dims, &W);
   if (ws_bytes < W.total) {
     set_error("workspace of %zu bytes is smaller than the %zu required", ws_bytes, W.total);
     return FAX_ERR_WORKSPACE;
   }
-  return block_bwd_impl(*dims, *params, x, dy, (const char*)saved, dx, *grads, accumulate != 0, (char*)ws,
-                        (hipStream_t)stream);
+  return block_bwd_impl(*dims, *params, x, dy, (const char*)saved, dx, *grads, accumulate != 0, dh1_partial, dh2_partial,
+                        (char*)ws, (hipStream_t)stream);
 }
 
-int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp, size_t n, const FaxAdamW* hp, int step,
-                   void* stream) {
+int fax_adamw_step(void* master, void* m, void* v, const void* grad, int grad_dtype, void* lowp, size_t n,
+                   const FaxAdamW* hp, int step, void* stream) {
+  if (grad_dtype != FAX_F32 && grad_dtype != FAX_BF16) { set_error("grad_dtype must be FAX_F32 or FAX_BF16"); return FAX_ERR_INVALID_ARG; }
   if (n == 0) return FAX_OK;
   FAX_TRY(check_ptr(master, "master"));
   FAX_TRY(check_ptr(m, "m"));
@@ -599,7 +605,7 @@ int fax_adamw_step(void* master, void* m, void* v, const void* grad, void* lowp,
   FAX_TRY(check_ptr(grad, "grad"));
   if (lowp && misaligned(lowp)) { set_error("lowp is not 16-byte aligned"); return FAX_ERR_INVALID_ARG; }
   FAX_TRY(check_adamw(hp, step));
-  return adamw((float*)master, (float*)m, (float*)v, (const float*)grad, lowp, n, *hp, step, (hipStream_t)stream);
+  return adamw((float*)master, (float*)m, (float*)v, grad, grad_dtype, lowp, n, *hp, step, (hipStream_t)stream);
 }
 
 int fax_adamw_block_step(const FaxBlockDims* dims, const FaxBlockTensors* master, const FaxBlockTensors* m,
@@ -783,7 +789,8 @@ int fax_train_step(const FaxModelDims* dims, const FaxModelTensors* params, cons
                  nullptr, w + W.dcur, (float*)grads->lnf_g, (float*)grads->lnf_b, acc, w + W.blk, s));
   for (int l = L - 1; l >= 0; l--)
     FAX_TRY(block_bwd_impl(bd, params->blocks[l], w + W.xs + W.x_stride * l, w + W.dcur,
-                           w + W.saved + W.saved_stride * l, w + W.dcur, grads->blocks[l], acc, w + W.blk, s));
+                           w + W.saved + W.saved_stride * l, w + W.dcur, grads->blocks[l], acc, nullptr, nullptr,
+                           w + W.blk, s));
   // embedding backward: token rows add onto the output projection's share; positions beyond S get zero
   if (!acc) FAX_TRY(fill_zero(grads->pos_emb, (size_t)dims->S_max * D * 4, s));
   FAX_TRY(embed_bwd(d.dtype, d.B, d.S, D, V, tokens, w + W.dcur, (float*)grads->tok_emb, (float*)grads->pos_emb, acc,

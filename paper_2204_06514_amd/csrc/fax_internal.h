@@ -161,8 +161,8 @@ struct AdamWQueue {
   hipStream_t s;
   double bytes = 0;
 };
-int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
-          hipStream_t s);
+int adamw(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, size_t n, const FaxAdamW& hp,
+          int step, hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // ---- measured ceilings (probes.hip) ---------------------------------------------------------------

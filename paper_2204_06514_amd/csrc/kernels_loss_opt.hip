@@ -424,15 +424,24 @@ __device__ __forceinline__ void adam_one(float g, float& p, float& m, float& v, 
   p = p * a.decay - a.lr * mh / (sqrtf(vh) + a.eps);
 }
 
+// G: the gradient's type, float or bf16_t (a caller that keeps its gradients in the compute precision)
+template <typename G>
 __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict__ p, float* __restrict__ m,
-                                                    float* __restrict__ v, const float* __restrict__ g,
+                                                    float* __restrict__ v, const G* __restrict__ g,
                                                     bf16_t* __restrict__ lowp, AdamScalars a) {
   const size_t nvec = n / 4;
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
     float4 pv = reinterpret_cast<float4*>(p)[i], mv = reinterpret_cast<float4*>(m)[i];
     float4 vv = reinterpret_cast<float4*>(v)[i];
-    const float4 gv = reinterpret_cast<const float4*>(g)[i];
+    float4 gv;
+    if constexpr (sizeof(G) == 4) {
+      gv = reinterpret_cast<const float4*>(g)[i];
+    } else {
+      union { uint2 u; bf16_t h[4]; } gk;
+      gk.u = reinterpret_cast<const uint2*>(g)[i];
+      gv = make_float4((float)gk.h[0], (float)gk.h[1], (float)gk.h[2], (float)gk.h[3]);
+    }
     adam_one(gv.x, pv.x, mv.x, vv.x, a);
     adam_one(gv.y, pv.y, mv.y, vv.y, a);
     adam_one(gv.z, pv.z, mv.z, vv.z, a);
@@ -449,7 +458,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict_
   // ragged tail
   for (size_t i = nvec * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
     float pp = p[i], mm = m[i], vv = v[i];
-    adam_one(g[i], pp, mm, vv, a);
+    adam_one((float)g[i], pp, mm, vv, a);
     p[i] = pp; m[i] = mm; v[i] = vv;
     if (lowp) lowp[i] = (bf16_t)pp;
   }
@@ -457,15 +466,20 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict_
 
 static AdamScalars adam_scalars(const FaxAdamW& hp, int step);
 
-int adamw(float* master, float* m, float* v, const float* grad, void* lowp, size_t n, const FaxAdamW& hp, int step,
-          hipStream_t s) {
+int adamw(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, size_t n, const FaxAdamW& hp,
+          int step, hipStream_t s) {
   if (n == 0) return FAX_OK;
-  Timed t_("adamw", WORK_BYTE, (lowp ? 30.0 : 28.0) * (double)n, s);
+  Timed t_("adamw", WORK_BYTE, ((lowp ? 30.0 : 28.0) - (grad_dtype == FAX_BF16 ? 2.0 : 0.0)) * (double)n, s);
   const AdamScalars a = adam_scalars(hp, step);
   size_t blocks = (n / 4 + 255) / 256;
   if (blocks < 1) blocks = 1;
   if (blocks > 256 * 16) blocks = 256 * 16;
-  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, grad, (bf16_t*)lowp, a);
+  if (grad_dtype == FAX_BF16)
+    hipLaunchKernelGGL(adamw_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, (const bf16_t*)grad,
+                       (bf16_t*)lowp, a);
+  else
+    hipLaunchKernelGGL(adamw_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, n, master, m, v, (const float*)grad,
+                       (bf16_t*)lowp, a);
   FAX_LAUNCH_CHECK("adamw");
   return FAX_OK;
 }

@@ -77,7 +77,11 @@ def run_block(sh, p, x, dy, gelu=None, partial=False, accumulate=False, grads_in
         for k in gd:
             gd[k].copy_(torch.from_numpy(grads_init[k].astype(np.float32)))
     dx = torch.empty_like(xd)
-    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, accumulate, ws, wsb)
+    # a tensor-parallel rank asks for the two input-gradient partial sums in buffers of its own;
+    # otherwise they stay in the workspace, at the offsets of fax_block_bwd_layout()
+    d1 = torch.empty_like(xd) if partial else None
+    d2 = torch.empty_like(xd) if partial else None
+    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, accumulate, d1, d2, ws, wsb)
     torch.cuda.synchronize()
     T, Hd = sh.T, sh.Hd
     out = {"y": to_np(y).reshape(x.shape), "dx": to_np(dx).reshape(x.shape),
@@ -89,8 +93,12 @@ def run_block(sh, p, x, dy, gelu=None, partial=False, accumulate=False, grads_in
     bl = fax.fax_block_bwd_layout(dims)
     bw = {"du": (bl.du, (T, sh.F)), "dh2": (bl.dh2, (T, sh.D)), "dx1": (bl.dx1, (T, sh.D)),
           "dctx": (bl.dctx, (T, Hd)), "dqkv": (bl.dqkv, (T, 3 * Hd)), "dh1": (bl.dh1, (T, sh.D))}
+    if partial:   # delivered to the caller's buffers; their workspace slots are not written
+        del bw["dh1"], bw["dh2"]
     out["bwd"] = {k: to_np(view_bytes(ws, o, s, td)) for k, (o, s) in bw.items()}
     if partial:
+        out["bwd"]["dh1"] = to_np(d1).reshape(T, sh.D)
+        out["bwd"]["dh2"] = to_np(d2).reshape(T, sh.D)
         out["p_attn"] = to_np(pa).reshape(x.shape)
         out["p_mlp"] = to_np(pm).reshape(x.shape)
     return out

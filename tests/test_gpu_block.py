@@ -68,7 +68,7 @@ def test_cfg1_fp32_block_then_adamw_step(generic):
     y, dx = torch.empty_like(xd), torch.empty_like(xd)
     gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
     fax.fax_block_fwd(dims, pd, xd, y, saved, None, None, ws, wsb)
-    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, ws, wsb)
+    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, None, None, ws, wsb)
     m = {k: torch.zeros_like(t) for k, t in pd.items()}
     v = {k: torch.zeros_like(t) for k, t in pd.items()}
     fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, m, v, gd)), None, fax.FaxAdamW(**ADAMW_DEFAULT), 1)

@@ -31,7 +31,7 @@ def _block_twice(sh, seed, flags=(0, 0)):
         y, pa, pm, dx = (torch.empty_like(xd) for _ in range(4))
         gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
         fax.fax_block_fwd(dims, pd, xd, y, saved, pa, pm, ws, wsb)
-        fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, ws, wsb)
+        fax.fax_block_bwd(dims, pd, xd, dyd, saved, dx, gd, 0, None, None, ws, wsb)
         torch.cuda.synchronize()
         bl = fax.fax_block_bwd_layout(dims)
         runs.append({"y": y, "p_attn": pa, "p_mlp": pm, "dx": dx, "saved": saved, "bwd": ws[:bl.dh1 + sh.T * sh.D * y.element_size()],
@@ -69,7 +69,7 @@ def test_the_second_stream_changes_no_bit(sh):
     y, pa, pm = (torch.empty_like(xd) for _ in range(3))
     gd = {k: torch.full(t.shape, 7.0, dtype=torch.float32, device=DEV) for k, t in pd.items()}
     fax.fax_block_fwd(dims, pd, xd, y, saved, pa, pm, ws, wsb)
-    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dyd, gd, 0, ws, wsb)      # dx aliases dy
+    fax.fax_block_bwd(dims, pd, xd, dyd, saved, dyd, gd, 0, None, None, ws, wsb)      # dx aliases dy
     torch.cuda.synchronize()
     assert torch.equal(dyd, a["dx"])
     for k in PARAM_NAMES:

@@ -44,7 +44,7 @@ def test_cfg2_two_layer_stack_with_adamw_full_size():
     for l in range(sh.L):
         fax.fax_block_fwd(dims, pd[l], xs[l], xs[l + 1], saved[l], None, None, ws, wsb)
     for l in reversed(range(sh.L)):
-        fax.fax_block_bwd(dims, pd[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gd[l], 0, ws, wsb)
+        fax.fax_block_bwd(dims, pd[l], xs[l], dyd if l == sh.L - 1 else dcur, saved[l], dcur, gd[l], 0, None, None, ws, wsb)
     master = [{k: t.float().clone() for k, t in p.items()} for p in pd]
     hp = fax.FaxAdamW(**ADAMW_DEFAULT)
     ms_, vs_ = [], []

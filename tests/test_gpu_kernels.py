@@ -243,7 +243,7 @@ def test_adamw_three_steps_and_bf16_copy(n):
     for t in range(1, 4):
         g = (rng.standard_normal(n) * 10 ** rng.uniform(-3, 1, n)).astype(np.float32).astype(np.float64)
         p, m, v = orc.adamw(p, m, v, g, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
-        fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), low, n, hp, t)
+        fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), fax.FAX_F32, low, n, hp, t)
         assert rel_max(to_np(pd), p) <= 1e-6
         assert rel_max(to_np(md), m) <= 1e-6 and rel_max(to_np(vd), v) <= 1e-6
         assert torch.equal(low, pd.to(torch.bfloat16))
@@ -251,8 +251,27 @@ def test_adamw_three_steps_and_bf16_copy(n):
     g = rng.standard_normal(n).astype(np.float32).astype(np.float64)
     p0 = to_np(pd)
     md.zero_(); vd.zero_()
-    fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), None, n, hp, 1)
+    fax.fax_adamw_step(pd, md, vd, to_dev(g, "f32"), fax.FAX_F32, None, n, hp, 1)
     assert rel_max(to_np(pd), p0 * (1 - 1e-5) - 1e-3 * g / (np.abs(g) + 1e-8)) <= 1e-6
+
+
+@pytest.mark.parametrize("n", [3, 4099, 1 << 18])
+def test_adamw_takes_gradients_in_bf16(n):
+    """grad_dtype = FAX_BF16: the same update from gradients stored in the compute precision (both
+    sides get the gradient already rounded to bf16; the arithmetic stays fp32)."""
+    rng = np.random.default_rng(n + 7)
+    p = rng.standard_normal(n).astype(np.float32).astype(np.float64)
+    m = np.zeros(n); v = np.zeros(n)
+    pd = to_dev(p, "f32"); md = torch.zeros(n, device=DEV); vd = torch.zeros(n, device=DEV)
+    low = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    hp = fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.01)
+    for t in range(1, 4):
+        g = _store(rng.standard_normal(n) * 10 ** rng.uniform(-3, 1, n), "bf16")
+        p, m, v = orc.adamw(p, m, v, g, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
+        fax.fax_adamw_step(pd, md, vd, to_dev(g, "bf16"), fax.FAX_BF16, low, n, hp, t)
+        assert rel_max(to_np(pd), p) <= 1e-6
+        assert rel_max(to_np(md), m) <= 1e-6 and rel_max(to_np(vd), v) <= 1e-6
+        assert torch.equal(low, pd.to(torch.bfloat16))
 
 
 def test_adamw_block_step_updates_all_twelve_tensors_like_the_single_tensor_call():
@@ -280,11 +299,11 @@ def test_adamw_block_step_updates_all_twelve_tensors_like_the_single_tensor_call
         assert rel_max(to_np(vd[k]), ref_v) <= 1e-6, k
         assert torch.equal(low[k], pd[k].to(torch.bfloat16)), k
         # and bit for bit what the one-tensor entry point computes
-        fax.fax_adamw_step(p1[k], m1[k], v1[k], gd[k], None, n, hp, 3)
+        fax.fax_adamw_step(p1[k], m1[k], v1[k], gd[k], fax.FAX_F32, None, n, hp, 3)
         assert torch.equal(p1[k], pd[k]) and torch.equal(m1[k], md[k]) and torch.equal(v1[k], vd[k]), k
     # without the low-precision copies
     fax.fax_adamw_block_step(dims, *(fax.block_tensors(t) for t in (pd, md, vd, gd)), None, hp, 4)
-    fax.fax_adamw_step(p1["w1"], m1["w1"], v1["w1"], gd["w1"], None, shapes["w1"], hp, 4)
+    fax.fax_adamw_step(p1["w1"], m1["w1"], v1["w1"], gd["w1"], fax.FAX_F32, None, shapes["w1"], hp, 4)
     assert torch.equal(p1["w1"], pd["w1"])
 
 

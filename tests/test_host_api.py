@@ -74,17 +74,23 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
         fax.fax_block_fwd(d, good, 4096, 4096, 4096, stream=0)
     assert "alias" in str(e.value)
     with pytest.raises(fax.FaxError) as e:
-        fax.fax_block_bwd(d, good, 4096, 4096, 4096, 4096, good, 0, 4096, 16, stream=0)
+        fax.fax_block_bwd(d, good, 4096, 4096, 4096, 4096, good, 0, None, None, 4096, 16, stream=0)
     assert e.value.status == fax.FAX_ERR_WORKSPACE
+    with pytest.raises(fax.FaxError) as e:                       # the optional partial-sum outputs are checked like the rest
+        fax.fax_block_bwd(d, good, 4096, 4096, 4096, 4096, good, 0, 4096 + 8, None, 4096, 1 << 40, stream=0)
+    assert "dh1_partial" in str(e.value) and "aligned" in str(e.value)
 
 
 def test_adamw_and_train_argument_checks():
     hp = fax.FaxAdamW(1e-3, 0.9, 0.999, 1e-8, 0.01)
     with pytest.raises(fax.FaxError):
-        fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, hp, 0, stream=0)       # step < 1
+        fax.fax_adamw_step(4096, 4096, 4096, 4096, fax.FAX_F32, None, 16, hp, 0, stream=0)       # step < 1
     with pytest.raises(fax.FaxError):
-        fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, fax.FaxAdamW(1e-3, 1.0, 0.999, 1e-8, 0.0), 1, stream=0)
-    fax.fax_adamw_step(None, None, None, None, None, 0, hp, 1, stream=0)            # n = 0 is a no-op
+        fax.fax_adamw_step(4096, 4096, 4096, 4096, fax.FAX_F32, None, 16, fax.FaxAdamW(1e-3, 1.0, 0.999, 1e-8, 0.0), 1, stream=0)
+    fax.fax_adamw_step(None, None, None, None, fax.FAX_F32, None, 0, hp, 1, stream=0)            # n = 0 is a no-op
+    with pytest.raises(fax.FaxError) as e:
+        fax.fax_adamw_step(4096, 4096, 4096, 4096, 7, None, 16, hp, 1, stream=0)                 # not a dtype
+    assert "grad_dtype" in str(e.value)
     md = fax.FaxModelDims(_dims(), 2, 100, 32, 0)                                   # S_max < S
     with pytest.raises(fax.FaxError):
         fax.fax_train_workspace_bytes(md)
@@ -119,7 +125,7 @@ def test_adamw_hyper_parameters_are_checked_by_every_entry_point_that_takes_them
                fax.FaxAdamW(float("nan"), 0.9, 0.999, 1e-8, 0.0)]
     for hp in bad_hps:
         with pytest.raises(fax.FaxError) as e:
-            fax.fax_adamw_step(4096, 4096, 4096, 4096, None, 16, hp, 1, stream=0)
+            fax.fax_adamw_step(4096, 4096, 4096, 4096, fax.FAX_F32, None, 16, hp, 1, stream=0)
         assert e.value.status == fax.FAX_ERR_INVALID_ARG
         with pytest.raises(fax.FaxError) as e:
             fax.fax_adamw_block_step(d, good, good, good, good, None, hp, 1, stream=0)
