@@ -284,6 +284,7 @@ struct EpiArgs {
   int splits;           // K ranges (fp32-output form); range r writes to C + r * split_stride
   size_t split_stride;  // in elements
   size_t colsum_stride; // likewise for the column sums: range r writes colsum + r * colsum_stride
+  int group;            // tile rows per column-major group of the tile walk (MFMA kernel)
 };
 
 template <typename T>

@@ -190,12 +190,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   // Tile number -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with
   // its own L2) and gridDim.x is a multiple of 8 whenever that matters, so a workgroup's tile
   // numbers all have its own residue mod 8; the number is first re-dealt so that each XCD owns a
-  // contiguous run of tiles, then tiles are walked in column-major groups of 8 tile-rows to keep
-  // the working set of A and B panels small.
+  // contiguous run of tiles, then tiles are walked in column-major groups of e.group (4 or 8, chosen
+  // on the host) tile-rows to keep the working set of A and B panels small.
   const int nt = tiles_m * tiles_n;
   auto tile_of = [&](int id, int& tm_i, int& tn_i) {
     if (nt % 8 == 0) id = (id % 8) * (nt / 8) + id / 8;
-    constexpr int GROUP = 8;
+    const int GROUP = e.group;
     const int per_group = GROUP * tiles_n;
     const int g = id / per_group;
     const int gm0 = g * GROUP;
@@ -532,6 +532,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// Tile rows per group of the tile walk (see tile_of in the kernel): the 32 tiles an XCD works on
+// at a time form a block of `group` tile rows x 32 / group tile columns.  8 x 4 and 4 x 8 fetch the
+// same twelve operand panels; measured inside the benchmark steps, 4 x 8 is the faster one wherever
+// the output is wide enough to hold whole blocks of eight columns and the contraction is long
+// (d_model 4096 block -0.8 %, the 12288-wide share -2 %, the 2048-wide model -1.2 %, the 1024-wide
+// one -1.6 %), and the slower one (+0.3 to 0.5 %) for the 768-wide model with its 3 to 12 tile
+// columns and K = 768, which therefore keeps 8 x 4.
+static int walk_group(int tiles_n, int K) { return (K >= 1024 && (tiles_n >= 16 || tiles_n % 8 == 0)) ? 4 : 8; }
+
 // Both heuristics are written for the 256 CUs of the MI355X.  No device query here on purpose:
 // plans decide workspace sizes, and those are computed on hosts without a GPU too (the launch
 // itself sizes its grid from the device's own CU count, see launch_mfma).
@@ -793,7 +802,7 @@ int gemm_mfma(const GemmArgs& g0, hipStream_t s) {
     g.accumulate = false;
   }
   EpiArgs e{g.bias, g.R, g.ldr, g.C, g.ldc, g.C2, g.ldc2, g.U, g.ldu, g.epi, g.gelu_form, g.c_f32 ? 1 : 0,
-            g.accumulate ? 1 : 0, g.colsum, splits, mn, (size_t)g.N};
+            g.accumulate ? 1 : 0, g.colsum, splits, mn, (size_t)g.N, walk_group(g.N / plan.tile_n, g.K)};
   if (plan.tile_n == 256) FAX_TRY((dispatch<256, 256>(g, e, s)));
   else if (plan.tile_m == 256) FAX_TRY((dispatch<256, 128>(g, e, s)));
   else FAX_TRY((dispatch<128, 128>(g, e, s)));
