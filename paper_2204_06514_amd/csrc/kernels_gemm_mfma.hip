@@ -133,7 +133,12 @@ __device__ __forceinline__ float4 ld_bf16x4(const void* base, size_t idx) {
 __device__ __forceinline__ void st_bf16x4(void* base, size_t idx, float4 a) {
   bf16x4 v;
   v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
-  *reinterpret_cast<bf16x4*>((bf16_t*)base + idx) = v;
+  // Streaming store: the tile is not read again by this kernel, and a round of tiles is as large as the
+  // L2s (32 x 128 KB per XCD against 4 MB), where it would push out the operand panels that the
+  // XCD's workgroups share.  Measured against plain stores, A-B-A-B on one box: the 768-wide model
+  // 64.8-66.2 -> 63.9-64.0 ms (forward 21.4-22.1 -> 20.55 ms), the 1024-wide one -0.6 %, d_model 4096
+  // unchanged.
+  __builtin_nontemporal_store(v, reinterpret_cast<bf16x4*>((bf16_t*)base + idx));
 }
 // `side` is the row's residual (R) or, for the GELU' flavour, the stored derivative (U), fetched by
 // the caller ahead of time so that its latency overlaps the LDS turn-around.
@@ -143,7 +148,9 @@ __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, f
   constexpr int KIND = em_kind(EM);
   if (KIND == EK_F32) {
     if (EM & EM_RES) { a.x += side.x; a.y += side.y; a.z += side.z; a.w += side.w; }
-    *reinterpret_cast<float4*>((float*)e.C + (size_t)m * e.ldc + n) = a;
+    typedef __attribute__((ext_vector_type(4))) float f32x4s;
+    const f32x4s av = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(av, reinterpret_cast<f32x4s*>((float*)e.C + (size_t)m * e.ldc + n));  // as st_bf16x4
     return;
   }
   if (EM & EM_C2) st_bf16x4(e.C2, (size_t)m * e.ldc2 + n, a);

@@ -412,6 +412,18 @@ int embed_bwd(int dtype, int B, int S, int D, int V, const int32_t* tokens, cons
 // ---------------------------------------------------------------------------------------------
 // AdamW: 16 B/param read (g, p, m, v) + 12 B/param written (+2 for the bf16 copy).
 // ---------------------------------------------------------------------------------------------
+// Streaming stores for values this kernel does not read again.
+__device__ __forceinline__ void nt_store4(float4* p, float4 v) {
+  typedef __attribute__((ext_vector_type(4))) float f4;
+  const f4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<f4*>(p));
+}
+__device__ __forceinline__ void nt_store2(uint2* p, uint2 v) {
+  typedef __attribute__((ext_vector_type(2))) unsigned u2;
+  const u2 x = {v.x, v.y};
+  __builtin_nontemporal_store(x, reinterpret_cast<u2*>(p));
+}
+
 struct AdamScalars {
   float b1, b2, one_m_b1, one_m_b2, inv_bc1, inv_bc2, lr, eps, decay;
 };
@@ -446,13 +458,13 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float* __restrict_
     adam_one(gv.y, pv.y, mv.y, vv.y, a);
     adam_one(gv.z, pv.z, mv.z, vv.z, a);
     adam_one(gv.w, pv.w, mv.w, vv.w, a);
-    reinterpret_cast<float4*>(p)[i] = pv;
-    reinterpret_cast<float4*>(m)[i] = mv;
-    reinterpret_cast<float4*>(v)[i] = vv;
+    nt_store4(reinterpret_cast<float4*>(p) + i, pv);
+    nt_store4(reinterpret_cast<float4*>(m) + i, mv);
+    nt_store4(reinterpret_cast<float4*>(v) + i, vv);
     if (lowp) {
       union { bf16_t h[4]; uint2 u; } pk;
       pk.h[0] = (bf16_t)pv.x; pk.h[1] = (bf16_t)pv.y; pk.h[2] = (bf16_t)pv.z; pk.h[3] = (bf16_t)pv.w;
-      reinterpret_cast<uint2*>(lowp)[i] = pk.u;
+      nt_store2(reinterpret_cast<uint2*>(lowp) + i, pk.u);
     }
   }
   // ragged tail
@@ -508,13 +520,13 @@ __global__ __launch_bounds__(256) void adamw_multi_kernel(AdamWBatch b, AdamScal
       adam_one(gv.y, pv.y, mv.y, vv.y, a);
       adam_one(gv.z, pv.z, mv.z, vv.z, a);
       adam_one(gv.w, pv.w, mv.w, vv.w, a);
-      reinterpret_cast<float4*>(p)[i] = pv;
-      reinterpret_cast<float4*>(m)[i] = mv;
-      reinterpret_cast<float4*>(v)[i] = vv;
+      nt_store4(reinterpret_cast<float4*>(p) + i, pv);
+      nt_store4(reinterpret_cast<float4*>(m) + i, mv);
+      nt_store4(reinterpret_cast<float4*>(v) + i, vv);
       if (lowp) {
         union { bf16_t h[4]; uint2 u; } pk;
         pk.h[0] = (bf16_t)pv.x; pk.h[1] = (bf16_t)pv.y; pk.h[2] = (bf16_t)pv.z; pk.h[3] = (bf16_t)pv.w;
-        reinterpret_cast<uint2*>(lowp)[i] = pk.u;
+        nt_store2(reinterpret_cast<uint2*>(lowp) + i, pk.u);
       }
     }
   }
