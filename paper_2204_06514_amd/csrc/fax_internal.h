@@ -211,6 +211,12 @@ template <> struct Vec16<float> {
   float4 raw;
   __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
   __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  // streaming store: for values that are too large to be found in a cache by whoever reads them next
+  __device__ __forceinline__ void store_nt(float* p) const {
+    typedef __attribute__((ext_vector_type(4))) float f4;
+    const f4 x = {raw.x, raw.y, raw.z, raw.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<f4*>(p));
+  }
   __device__ __forceinline__ float get(int i) const { return reinterpret_cast<const float*>(&raw)[i]; }
   __device__ __forceinline__ void set(int i, float v) { reinterpret_cast<float*>(&raw)[i] = v; }
 };
@@ -219,6 +225,11 @@ template <> struct Vec16<bf16_t> {
   uint4 raw;
   __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
   __device__ __forceinline__ void store(bf16_t* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ void store_nt(bf16_t* p) const {
+    typedef __attribute__((ext_vector_type(4))) unsigned u4;
+    const u4 x = {raw.x, raw.y, raw.z, raw.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<u4*>(p));
+  }
   __device__ __forceinline__ float get(int i) const {
     uint32_t w = reinterpret_cast<const uint32_t*>(&raw)[i >> 1];
     return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));

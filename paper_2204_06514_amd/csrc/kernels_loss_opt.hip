@@ -111,7 +111,7 @@ __global__ __launch_bounds__(CE_MAX_THREADS) void ce_cached_kernel(int N, int V,
       Vv o;
 #pragma unroll
       for (int e = 0; e < Vv::N; e++) o.set(e, g[e]);
-      o.store(dz + (size_t)c * Vv::N);
+      o.store_nt(dz + (size_t)c * Vv::N);  // gigabytes of gradient: streaming (-3 % on this kernel; the same store for LayerNorm's output cost the next GEMM more than it saved)
     }
   }
 }
