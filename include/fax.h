@@ -180,6 +180,16 @@ typedef struct FaxGemmPlan {
 } FaxGemmPlan;
 int fax_gemm_plan(int M, int N, int K, int c_f32, FaxGemmPlan* out);
 
+/* Host-only: the order in which the bulk launch of that plan hands out its output tiles.  Work item
+ * number i (workgroup b of the persistent kernel takes i = b, b + grid, ...) is the tile at tile
+ * row tile_row[i], tile column tile_col[i]; *count receives the number of tiles (at most
+ * `capacity` entries are written), *group the kind of walk: 8 or 4 tile rows per column-major
+ * group, or 0 for the walk that lays the eight XCDs' blocks of a round side by side in a 16 x 16
+ * block of tiles.  count = 0 and group = -1 when no tile class divides the shape.
+ * Exposed so that a test can check that every walk visits every tile exactly once. */
+int fax_gemm_tile_walk(int M, int N, int K, int c_f32, int32_t* tile_row, int32_t* tile_col, int capacity,
+                       int* count, int* group);
+
 /*
  * Forward pass of one pre-LayerNorm decoder block (Fig. 1; forward phase of Fig. 4):
  *   h1 = LN(x; ln1);  qkv = h1 Wqkv + bqkv;  ctx = causal softmax(Q K^T / sqrt(dh)) V per head;

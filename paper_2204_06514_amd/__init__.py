@@ -100,6 +100,7 @@ def _load():
         "fax_last_error": (C.c_char_p, []),
         "fax_block_dims_check": (i32, [P(FaxBlockDims)]),
         "fax_gemm_plan": (i32, [i32, i32, i32, i32, P(FaxGemmPlan)]),
+        "fax_gemm_tile_walk": (i32, [i32, i32, i32, i32, vp, vp, i32, P(C.c_int), P(C.c_int)]),
         "fax_block_saved_layout": (i32, [P(FaxBlockDims), P(FaxSavedLayout)]),
         "fax_block_bwd_layout": (i32, [P(FaxBlockDims), P(FaxBwdLayout)]),
         "fax_block_workspace_bytes": (i32, [P(FaxBlockDims), P(sz)]),
@@ -205,6 +206,17 @@ def fax_gemm_plan(M, N, K, c_f32=0):
     out = FaxGemmPlan()
     _check(_lib.fax_gemm_plan(M, N, K, int(c_f32), C.byref(out)))
     return (out.tail, out.tile_m, out.tile_n, out.splits)
+
+
+def fax_gemm_tile_walk(M, N, K, c_f32=0):
+    """-> (group, [(tile_row, tile_col), ...] in work-item order) of the plan's bulk launch (host only)."""
+    count, group = C.c_int(0), C.c_int(0)
+    _check(_lib.fax_gemm_tile_walk(M, N, K, int(c_f32), None, None, 0, C.byref(count), C.byref(group)))
+    n = count.value
+    rows = (C.c_int32 * max(n, 1))(); cols = (C.c_int32 * max(n, 1))()
+    _check(_lib.fax_gemm_tile_walk(M, N, K, int(c_f32), C.cast(rows, C.c_void_p), C.cast(cols, C.c_void_p), n,
+                                   C.byref(count), C.byref(group)))
+    return group.value, [(rows[i], cols[i]) for i in range(n)]
 
 
 def fax_block_saved_layout(dims):

@@ -517,6 +517,15 @@ int fax_gemm_plan(int M, int N, int K, int c_f32, FaxGemmPlan* out) {
   return FAX_OK;
 }
 
+int fax_gemm_tile_walk(int M, int N, int K, int c_f32, int32_t* tile_row, int32_t* tile_col, int capacity, int* count,
+                       int* group) {
+  if (!count || !group) { set_error("count or group is NULL"); return FAX_ERR_INVALID_ARG; }
+  if (capacity < 0 || (capacity > 0 && (!tile_row || !tile_col))) { set_error("tile_row / tile_col missing"); return FAX_ERR_INVALID_ARG; }
+  if (M <= 0 || N <= 0 || K <= 0) { set_error("non-positive GEMM size %d x %d x %d", M, N, K); return FAX_ERR_INVALID_ARG; }
+  gemm_tile_walk_query(M, N, K, c_f32 != 0, tile_row, tile_col, capacity, count, group);
+  return FAX_OK;
+}
+
 int fax_block_saved_layout(const FaxBlockDims* dims, FaxSavedLayout* out) {
   FAX_TRY(check_dims(dims));
   if (!out) { set_error("out is NULL"); return FAX_ERR_INVALID_ARG; }

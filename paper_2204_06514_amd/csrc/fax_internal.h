@@ -75,6 +75,7 @@ struct GemmSplitPlan {
 GemmSplitPlan gemm_split_plan(int M, int N, int K);
 size_t gemm_split_ws_bytes(int M, int N, int K);
 GemmSplitPlan gemm_plan_query(int M, int N, int K, bool f32_out, int* tail);
+int gemm_tile_walk_query(int M, int N, int K, bool f32_out, int* tm, int* tn, int capacity, int* count, int* group);
 // Predicted duration of gemm() on this shape from the same cost model (host only), microseconds.
 double gemm_time_estimate_us(int M, int N, int K, bool f32_out);
 int gemm_mfma(const GemmArgs& g, hipStream_t s);

@@ -177,6 +177,30 @@ __device__ __forceinline__ void mfma_epilogue4(const EpiArgs& e, int m, int n, f
   st_bf16x4(e.C, (size_t)m * e.ldc + n, a);
 }
 
+// Tile number -> tile of the persistent kernel (comment at its use below).  Host and device: the
+// host copy lets the tests check that every walk visits every tile exactly once.
+__host__ __device__ inline void tile_walk(int id, int tiles_m, int tiles_n, int group, int& tm_i, int& tn_i) {
+  if (group == 0) {
+    // 256 workgroups, tile counts that are multiples of 16 both ways: round number id >> 8 is a
+    // 16 x 16 block of tiles (walked down the tile rows first), XCD x takes the 4 x 8 block at
+    // (x & 3, x >> 2) of it, its workgroup j the tile (j & 3, j >> 2) of that.  The eight XCDs then
+    // work on 16 + 16 operand panels at any time instead of 32 + 8.
+    const int x = id & 7, j = (id >> 3) & 31, sb = id >> 8;
+    const int sbm = tiles_m >> 4;
+    tm_i = ((sb % sbm) << 4) + ((x & 3) << 2) + (j & 3);
+    tn_i = ((sb / sbm) << 4) + ((x >> 2) << 3) + (j >> 2);
+    return;
+  }
+  const int nt = tiles_m * tiles_n;
+  if (nt % 8 == 0) id = (id % 8) * (nt / 8) + id / 8;
+  const int per_group = group * tiles_n;
+  const int g = id / per_group;
+  const int gm0 = g * group;
+  const int gsz = group < tiles_m - gm0 ? group : tiles_m - gm0;
+  tm_i = gm0 + (id % per_group) % gsz;
+  tn_i = (id % per_group) / gsz;
+}
+
 template <int BM, int BN, bool A_KC, bool B_KC, int EM>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ B, int ldb, EpiArgs e, int tiles_m,
@@ -201,27 +225,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   // on the host) tile-rows to keep the working set of A and B panels small.  e.group = 0 selects the
   // walk in which the XCDs' blocks of a round lie side by side (below).
   const int nt = tiles_m * tiles_n;
-  auto tile_of = [&](int id, int& tm_i, int& tn_i) {
-    if (e.group == 0) {
-      // 256 workgroups, tile counts that are multiples of 16 both ways: round number id >> 8 is a
-      // 16 x 16 block of tiles (walked down the tile rows first), XCD x takes the 4 x 8 block at
-      // (x & 3, x >> 2) of it, its workgroup j the tile (j & 3, j >> 2) of that.  The eight XCDs then
-      // work on 16 + 16 operand panels at any time instead of 32 + 8.
-      const int x = id & 7, j = (id >> 3) & 31, sb = id >> 8;
-      const int sbm = tiles_m >> 4;
-      tm_i = ((sb % sbm) << 4) + ((x & 3) << 2) + (j & 3);
-      tn_i = ((sb / sbm) << 4) + ((x >> 2) << 3) + (j >> 2);
-      return;
-    }
-    if (nt % 8 == 0) id = (id % 8) * (nt / 8) + id / 8;
-    const int GROUP = e.group;
-    const int per_group = GROUP * tiles_n;
-    const int g = id / per_group;
-    const int gm0 = g * GROUP;
-    const int gsz = min(GROUP, tiles_m - gm0);
-    tm_i = gm0 + (id % per_group) % gsz;
-    tn_i = (id % per_group) / gsz;
-  };
+  auto tile_of = [&](int id, int& tm_i, int& tn_i) { tile_walk(id, tiles_m, tiles_n, e.group, tm_i, tn_i); };
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // in a scalar register: LDS segment addresses stay scalar
@@ -656,6 +660,22 @@ GemmSplitPlan gemm_plan_query(int M, int N, int K, bool f32_out, int* tail) {
   if (td == 1) return plan_tiles(M - 128, N, K, f32_out, f32_out);
   if (td == 2) return plan_tiles(M, N - 128, K, f32_out, false);  // the strip keeps C's leading dimension: no split
   return plan_tiles(M, N, K, f32_out, f32_out);
+}
+
+// The tile walk of the main launch of a product (not of the 128-wide strip an odd multiple of 128
+// leaves over), as a table: tile number -> (tile row, tile column).  For the tests.
+int gemm_tile_walk_query(int M, int N, int K, bool f32_out, int* tm, int* tn, int capacity, int* count, int* group) {
+  int tail = 0;
+  const GemmSplitPlan plan = gemm_plan_query(M, N, K, f32_out, &tail);
+  if (plan.tile_m == 0) { *count = 0; *group = -1; return 0; }
+  const int tiles_m = (tail == 1 ? M - 128 : M) / plan.tile_m, tiles_n = (tail == 2 ? N - 128 : N) / plan.tile_n;
+  int grp = walk_group(tiles_m, tiles_n, K, plan.splits);
+  const int nt = tiles_m * tiles_n;
+  const int slots = (plan.tile_m == 128 && nt * plan.splits <= 2 * kCUs) ? 2 * kCUs : kCUs;
+  if (grp == 0 && (nt < slots ? nt : slots) != 256) grp = 4;  // as launch_mfma decides
+  *group = grp; *count = nt;
+  for (int id = 0; id < nt && id < capacity; id++) tile_walk(id, tiles_m, tiles_n, grp, tm[id], tn[id]);
+  return 0;
 }
 
 // partial products, then partial column sums

@@ -167,6 +167,51 @@ def test_gemm_plan_query():
         fax.fax_gemm_plan(0, 128, 64)
 
 
+def test_gemm_tile_walks_visit_every_tile_once():
+    """The persistent GEMM hands its output tiles to the workgroups in one of three orders, chosen per
+    shape.  Each must be a bijection onto the tile grid; the side-by-side walk must give every round of
+    256 work items a 16 x 16 block of tiles and every XCD (work items with equal number mod 8) a 4 x 8
+    block of it; the grouped walks must give an XCD's 32 tiles of a round at most 12 operand panels
+    when the shape holds whole blocks."""
+    shapes = [  # the benchmark shapes: forward, input-gradient and weight-gradient products
+        (8192, 12288, 4096, 0), (8192, 4096, 4096, 0), (8192, 16384, 4096, 0), (8192, 4096, 16384, 0),
+        (4096, 12288, 8192, 1), (4096, 4096, 8192, 1), (4096, 16384, 8192, 1), (16384, 4096, 8192, 1),
+        (16384, 4608, 12288, 0), (16384, 12288, 1536, 0), (16384, 6144, 12288, 0), (12288, 4608, 16384, 1),
+        (16384, 6144, 2048, 0), (16384, 2048, 8192, 0), (2048, 8192, 16384, 1),
+        (65536, 2304, 768, 0), (65536, 768, 3072, 0), (768, 3072, 65536, 1), (65536, 50304, 768, 0), (50304, 768, 65536, 1),
+        (8192, 3072, 1024, 0), (1024, 4096, 8192, 1), (2048, 1920, 5120, 0), (2048, 5120, 640, 0), (5120, 2560, 2048, 1),
+        # odd tile counts and single rows / columns of tiles
+        (256, 256, 64, 0), (1280, 256, 1024, 0), (256, 3328, 2048, 0), (2304, 1792, 4096, 0), (128, 128, 64, 0)]
+    seen_groups = set()
+    for M, N, K, f32 in shapes:
+        tail, tile_m, tile_n, splits = fax.fax_gemm_plan(M, N, K, f32)
+        group, walk = fax.fax_gemm_tile_walk(M, N, K, f32)
+        tiles_m = (M - 128 if tail == 1 else M) // tile_m
+        tiles_n = (N - 128 if tail == 2 else N) // tile_n
+        assert len(walk) == tiles_m * tiles_n, (M, N, K)
+        assert sorted(walk) == [(r, c) for r in range(tiles_m) for c in range(tiles_n)], (M, N, K, group)
+        seen_groups.add(group)
+        if group == 0:
+            assert tiles_m % 16 == 0 and tiles_n % 16 == 0 and splits == 1
+            for rnd in range(len(walk) // 256):
+                blk = walk[256 * rnd:256 * rnd + 256]
+                r0, c0 = min(r for r, _ in blk), min(c for _, c in blk)
+                assert r0 % 16 == 0 and c0 % 16 == 0
+                assert all(r0 <= r < r0 + 16 and c0 <= c < c0 + 16 for r, c in blk)
+                for x in range(8):
+                    mine = blk[x::8]
+                    assert len({r for r, _ in mine}) == 4 and len({c for _, c in mine}) == 8, (M, N, K, rnd, x)
+        elif len(walk) % 256 == 0 and tiles_n % (32 // group) == 0 and tiles_m % group == 0 and (len(walk) // 8) % 32 == 0:
+            for rnd in range(len(walk) // 256):
+                blk = walk[256 * rnd:256 * rnd + 256]
+                for x in range(8):
+                    mine = blk[x::8]
+                    assert len({r for r, _ in mine}) + len({c for _, c in mine}) <= 12, (M, N, K, group, rnd, x)
+    assert seen_groups >= {0, 4, 8}
+    # no tile class: nothing to walk
+    assert fax.fax_gemm_tile_walk(100, 72, 64, 0) == (-1, [])
+
+
 def test_static_cross_entropy_checks_its_arguments_before_any_launch():
     assert fax.fax_cross_entropy_static_max_rows() == 1 << 18
     with pytest.raises(fax.FaxError) as e:
